@@ -1,0 +1,158 @@
+/*
+ * uniep_moe.h -- C ABI of the MI355X (gfx950) fused MoE layer.
+ *
+ * One GPU's share of the expert-parallel MoE hot path described in the UniEP
+ * paper: deterministic token mapping (Section 3.1, Algorithm 1), then
+ * dispatch -> grouped GEMM (gate/up) -> SwiGLU -> grouped GEMM (down) ->
+ * weighted combine (Section 2.1 "Forward Propagation", Sections 3.1-3.2), run
+ * as one persistent work-queue kernel with a global-memory scoreboard
+ * (Section 3.1 "Scoreboard-based Synchronization", "Dynamic Scheduling";
+ * Listing 1), and the matching backward pass (Section 2.1 "Backward
+ * Propagation": input gradients and the transposed grouped GEMM for weight
+ * gradients, reduced in the order the token mapping fixes).
+ *
+ * Conventions for every entry point
+ *   - All data pointers are DEVICE pointers (HIP global memory) unless a
+ *     parameter is marked "host".  moe_shape_t / moe_routing_t / moe_opts_t
+ *     structs themselves live in host memory.
+ *   - The caller owns every buffer.  The library allocates nothing, keeps no
+ *     state between calls, enqueues all work on `stream` (a hipStream_t passed
+ *     as void*; NULL = the default stream) and never synchronises with the
+ *     host: the number of routed rows and all tile tables stay on the device.
+ *   - Arrays are dense row-major.  bf16 tensors are passed as void*.
+ *   - Outputs are overwritten, never accumulated into.
+ *   - Return value: MOE_OK or a negative error code.  All argument, shape and
+ *     workspace checks happen before anything is enqueued, so a failed call
+ *     has no effect.
+ *   - Base pointers of bf16 tensors and of the workspace must be 16-byte
+ *     aligned (256-byte for workspaces).
+ *   - Two calls that share a workspace must be ordered on the stream.
+ *
+ * Shape limits (MOE_ERR_SHAPE otherwise): 1 <= k <= 16, k <= E <= 1024,
+ * 0 <= e_start, 1 <= e_count, e_start + e_count <= E, d and I multiples of 64,
+ * T >= 0 (T == 0 is a no-op apart from zeroed counts/offsets), T*k < 2^30
+ * (byte offsets inside the kernels are 64-bit).
+ */
+#ifndef UNIEP_MOE_H
+#define UNIEP_MOE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MOE_OK 0
+#define MOE_ERR_ARG (-1)       /* NULL or misaligned pointer */
+#define MOE_ERR_SHAPE (-2)     /* shape outside the limits above */
+#define MOE_ERR_WORKSPACE (-3) /* workspace / saved buffer too small */
+#define MOE_ERR_HIP (-4)       /* a HIP runtime call failed (launch, attribute) */
+#define MOE_ERR_DEVICE (-5)    /* reported by moe_device_status: a kernel gave up a bounded wait */
+
+/* Problem shape; all sizes in elements.  Local experts are
+ * [e_start, e_start + e_count): with N_epr experts per rank this is rank
+ * r_tgt = e / N_epr, local id e_loc = e % N_epr of Algorithm 1 (lines 5-6). */
+typedef struct {
+    int32_t T;       /* tokens resident on this GPU (N_tok) */
+    int32_t d;       /* hidden size (H_dim) */
+    int32_t E;       /* experts the router ranks (N_exp) */
+    int32_t k;       /* top-k */
+    int32_t I;       /* expert intermediate size (H_inter) */
+    int32_t e_start; /* first local expert */
+    int32_t e_count; /* number of local experts */
+} moe_shape_t;
+
+/* Output of moe_route / input of forward and backward (device pointers).
+ * A = offsets[e_count] is the number of (token, slot) assignments that land on
+ * local experts; "row" r in [0, A) is a position in the expert-sorted order. */
+typedef struct {
+    const int32_t* topk_idx; /* [T,k]  expert id of slot j (descending logit; ties: lower id) */
+    const float* topk_w;     /* [T,k]  gate: softmax renormalised over the k selected */
+    const int32_t* counts;   /* [e_count]    C_exp: rows per local expert */
+    const int32_t* offsets;  /* [e_count+1]  O_exp: exclusive prefix sum of counts */
+    const int32_t* perm;     /* [T*k]  row -> flat slot t*k+j; entries >= A are -1 */
+    const int32_t* inv_perm; /* [T,k]  flat slot -> row, or -1 if the expert is not local */
+} moe_routing_t;
+
+/* Launch options (host struct; NULL = all defaults). */
+typedef struct {
+    int32_t schedule; /* 0 = default (persistent), 1 = persistent work-queue megakernel,
+                         2 = staged: one launch per phase (same tile code; for profiling) */
+    int32_t workers;  /* persistent workgroups; 0 = one per resident slot (never more than
+                         can be co-resident: the deadlock-freedom condition of Section 3.1) */
+    int32_t spin_limit_ms; /* bound on every scoreboard wait; 0 = 2000 ms.  A wait that
+                              exceeds it sets MOE_ERR_DEVICE in the workspace and drains */
+    int32_t tile_rows;     /* rows per GEMM row tile: 0 = chosen from the shape, or 128 / 256 */
+    int32_t reserved[4];   /* must be 0 */
+} moe_opts_t;
+
+/* Bytes each call needs (host outputs; any may be NULL).  `saved_bytes` is the
+ * size of the optional activation stash forward fills for backward. */
+int moe_workspace_bytes(const moe_shape_t* shape, size_t* route_ws, size_t* fwd_ws,
+                        size_t* bwd_ws, size_t* saved_bytes);
+
+/* Byte offsets inside the `saved` stash (host outputs), for a given shape:
+ *   gu  [A_cap, 2*I] bf16  per row: G (I values) then U (I values), A_cap = T*k
+ *   h   [A_cap, I]   bf16  silu(G)*U
+ *   o   [A_cap, d]   bf16  expert outputs before the combine
+ * Rows at and beyond A are unspecified. */
+int moe_saved_layout(const moe_shape_t* shape, size_t* off_gu, size_t* off_h, size_t* off_o);
+
+/* Routing and deterministic token mapping (Section 2.1 gating; Algorithm 1,
+ * lines 1-2 and the local stable order M_loc, with one rank: base_off = 0).
+ *   logits   [T,E] fp32, finite.  Selection is on the raw logits: larger
+ *            first, equal values -> lower expert id first; slot j is the j-th
+ *            in that order.  Gate = softmax over all E renormalised over the k
+ *            selected.
+ * Writes the six arrays of moe_routing_t (the struct's pointers are used as
+ * outputs here).  Row of flat slot f = t*k+j with local expert e:
+ *   offsets[e - e_start] + #{f' < f : topk_idx[f'] == e}
+ * i.e. a stable sort of the flat slots by expert, computed without atomics on
+ * positions, so it is identical on every run. */
+int moe_route(const moe_shape_t* shape, const float* logits, const moe_routing_t* out,
+              void* ws, size_t ws_bytes, void* stream);
+
+/* Forward: y[t] = sum_j topk_w[t,j] * o[row(t,j)] over the local slots of t in
+ * slot order, fp32 accumulate, where for row r of local expert e holding token
+ * t:  h = silu(x[t] W_gate[e]) * (x[t] W_up[e]),  o[r] = h W_down[e]
+ * (Section 2.1; combine only after all k contributions exist and in one fixed
+ * order, Section 3.2).  bf16 in, fp32 accumulate, h / o / y rounded to bf16.
+ *   x       [T,d] bf16
+ *   w_gate  [e_count,d,I] bf16,  w_up [e_count,d,I] bf16,  w_down [e_count,I,d] bf16
+ *   y       [T,d] bf16 (tokens with no local slot get zeros)
+ *   saved   NULL, or saved_bytes of device memory that receives G,U,h,o for backward
+ *   ws      fwd_ws bytes */
+int moe_fused_forward(const moe_shape_t* shape, const void* x, const void* w_gate,
+                      const void* w_up, const void* w_down, const moe_routing_t* routing,
+                      void* y, void* saved, void* ws, size_t ws_bytes, const moe_opts_t* opts,
+                      void* stream);
+
+/* Backward of the above given dy [T,d] bf16 (Section 2.1 "Backward
+ * Propagation"): dO[r] = topk_w * dy[t];  dH = dO W_down^T;  SwiGLU backward;
+ * dXp = dG W_gate^T + dU W_up^T;  dx[t] = sum_j dXp[row(t,j)] in slot order;
+ * dW_down[e] = h_e^T dO_e, dW_gate[e] = x_e^T dG_e, dW_up[e] = x_e^T dU_e, each
+ * reduced over the expert's rows in row order (fixed by the token mapping, so
+ * bitwise reproducible).  Experts with no rows get exact zeros.
+ *   saved    the stash a forward call with the same inputs filled (required)
+ *   dx       [T,d] bf16;  dw_gate, dw_up [e_count,d,I] bf16;  dw_down [e_count,I,d] bf16
+ *   dtopk_w  [T,k] fp32 = <dy[t], o[row(t,j)]> (0 for non-local slots), or NULL
+ *   ws       bwd_ws bytes */
+int moe_fused_backward(const moe_shape_t* shape, const void* dy, const void* x,
+                       const void* w_gate, const void* w_up, const void* w_down,
+                       const moe_routing_t* routing, const void* saved, void* dx, void* dw_gate,
+                       void* dw_up, void* dw_down, float* dtopk_w, void* ws, size_t ws_bytes,
+                       const moe_opts_t* opts, void* stream);
+
+/* Synchronises `stream`, reads the status word a forward/backward call left in
+ * its workspace and returns MOE_OK or MOE_ERR_DEVICE (test and debug aid; the
+ * hot path never calls it). */
+int moe_device_status(const void* ws, void* stream);
+
+/* Static string for a return code. */
+const char* moe_status_string(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* UNIEP_MOE_H */

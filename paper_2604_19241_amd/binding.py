@@ -1,0 +1,210 @@
+"""Thin ctypes binding of libuniep_moe.so (include/uniep_moe.h).
+
+Argument marshalling only: torch supplies device memory and the current HIP
+stream; every step of the hot path runs in the library's kernels.  There is
+no CPU fallback: a missing library or a failed call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+from dataclasses import dataclass
+from pathlib import Path
+
+import torch
+
+_PKG = Path(__file__).resolve().parent
+LIB_PATH = _PKG / "libuniep_moe.so"
+
+MOE_OK = 0
+MOE_ERR_ARG, MOE_ERR_SHAPE, MOE_ERR_WORKSPACE, MOE_ERR_HIP, MOE_ERR_DEVICE = -1, -2, -3, -4, -5
+
+EXPORTS = ("moe_workspace_bytes", "moe_saved_layout", "moe_route", "moe_fused_forward",
+           "moe_fused_backward", "moe_device_status", "moe_status_string")
+
+
+class MoEShape(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("T", "d", "E", "k", "I", "e_start", "e_count")]
+
+
+class MoERoutingC(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in
+                ("topk_idx", "topk_w", "counts", "offsets", "perm", "inv_perm")]
+
+
+class MoEOpts(ctypes.Structure):
+    _fields_ = [("schedule", ctypes.c_int32), ("workers", ctypes.c_int32),
+                ("spin_limit_ms", ctypes.c_int32), ("tile_rows", ctypes.c_int32),
+                ("reserved", ctypes.c_int32 * 4)]
+
+
+class MoEError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {status_string(code)} ({code})")
+
+
+_lib = None
+
+
+def load_library():
+    """Load the HIP library; raises if it was not built (no fallback exists)."""
+    global _lib
+    if _lib is None:
+        if not LIB_PATH.exists():
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2604_19241_amd.build` "
+                "(hipcc, gfx950). There is no CPU fallback.")
+        lib = ctypes.CDLL(str(LIB_PATH))
+        lib.moe_status_string.restype = ctypes.c_char_p
+        lib.moe_status_string.argtypes = [ctypes.c_int]
+        for name in EXPORTS:
+            getattr(lib, name)   # AttributeError if a declared symbol is not exported
+        _lib = lib
+    return _lib
+
+
+def status_string(code: int) -> str:
+    return load_library().moe_status_string(int(code)).decode()
+
+
+def _check(code: int, where: str):
+    if code != MOE_OK:
+        raise MoEError(code, where)
+
+
+def make_shape(T, d, E, k, I, e_start=0, e_count=None) -> MoEShape:
+    return MoEShape(int(T), int(d), int(E), int(k), int(I), int(e_start),
+                    int(E if e_count is None else e_count))
+
+
+def make_opts(schedule=0, workers=0, spin_limit_ms=0, tile_rows=0) -> MoEOpts:
+    o = MoEOpts()
+    o.schedule, o.workers, o.spin_limit_ms, o.tile_rows = schedule, workers, spin_limit_ms, tile_rows
+    return o
+
+
+def _ptr(t):
+    return ctypes.c_void_p(0 if t is None else t.data_ptr())
+
+
+def _stream(device) -> ctypes.c_void_p:
+    return ctypes.c_void_p(torch.cuda.current_stream(device).cuda_stream)
+
+
+def moe_workspace_bytes(shape: MoEShape) -> dict:
+    vals = [ctypes.c_size_t(0) for _ in range(4)]
+    _check(load_library().moe_workspace_bytes(ctypes.byref(shape), *[ctypes.byref(v) for v in vals]),
+           "moe_workspace_bytes")
+    return dict(zip(("route", "fwd", "bwd", "saved"), (int(v.value) for v in vals)))
+
+
+def moe_saved_layout(shape: MoEShape) -> dict:
+    vals = [ctypes.c_size_t(0) for _ in range(3)]
+    _check(load_library().moe_saved_layout(ctypes.byref(shape), *[ctypes.byref(v) for v in vals]),
+           "moe_saved_layout")
+    return dict(zip(("gu", "h", "o"), (int(v.value) for v in vals)))
+
+
+@dataclass
+class Routing:
+    topk_idx: torch.Tensor   # [T,k] i32
+    topk_w: torch.Tensor     # [T,k] f32
+    counts: torch.Tensor     # [e_count] i32
+    offsets: torch.Tensor    # [e_count+1] i32
+    perm: torch.Tensor       # [T*k] i32
+    inv_perm: torch.Tensor   # [T,k] i32
+
+    def c_struct(self) -> MoERoutingC:
+        return MoERoutingC(*(t.data_ptr() for t in (self.topk_idx, self.topk_w, self.counts,
+                                                    self.offsets, self.perm, self.inv_perm)))
+
+
+def _ws(nbytes: int, device) -> torch.Tensor:
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def moe_route(shape: MoEShape, logits: torch.Tensor, ws: torch.Tensor | None = None) -> Routing:
+    assert logits.is_cuda and logits.dtype == torch.float32 and logits.is_contiguous()
+    assert tuple(logits.shape) == (shape.T, shape.E)
+    dev = logits.device
+    T, k, ec = shape.T, shape.k, shape.e_count
+    r = Routing(torch.empty((T, k), dtype=torch.int32, device=dev),
+                torch.empty((T, k), dtype=torch.float32, device=dev),
+                torch.empty(ec, dtype=torch.int32, device=dev),
+                torch.empty(ec + 1, dtype=torch.int32, device=dev),
+                torch.empty(T * k, dtype=torch.int32, device=dev),
+                torch.empty((T, k), dtype=torch.int32, device=dev))
+    if ws is None:
+        ws = _ws(moe_workspace_bytes(shape)["route"], dev)
+    cs = r.c_struct()
+    _check(load_library().moe_route(ctypes.byref(shape), _ptr(logits), ctypes.byref(cs), _ptr(ws),
+                                    ctypes.c_size_t(ws.numel()), _stream(dev)), "moe_route")
+    return r
+
+
+def moe_fused_forward(shape: MoEShape, x, w_gate, w_up, w_down, routing: Routing, y=None,
+                      saved: torch.Tensor | None = None, ws: torch.Tensor | None = None,
+                      opts: MoEOpts | None = None) -> torch.Tensor:
+    dev = x.device
+    for t in (x, w_gate, w_up, w_down):
+        assert t.is_cuda and t.dtype == torch.bfloat16 and t.is_contiguous()
+    assert tuple(x.shape) == (shape.T, shape.d)
+    assert tuple(w_gate.shape) == (shape.e_count, shape.d, shape.I) == tuple(w_up.shape)
+    assert tuple(w_down.shape) == (shape.e_count, shape.I, shape.d)
+    if y is None:
+        y = torch.empty((shape.T, shape.d), dtype=torch.bfloat16, device=dev)
+    if ws is None:
+        ws = _ws(moe_workspace_bytes(shape)["fwd"], dev)
+    cs = routing.c_struct()
+    _check(load_library().moe_fused_forward(
+        ctypes.byref(shape), _ptr(x), _ptr(w_gate), _ptr(w_up), _ptr(w_down), ctypes.byref(cs),
+        _ptr(y), _ptr(saved), _ptr(ws), ctypes.c_size_t(ws.numel()),
+        ctypes.byref(opts) if opts is not None else None, _stream(dev)), "moe_fused_forward")
+    return y
+
+
+def moe_fused_backward(shape: MoEShape, dy, x, w_gate, w_up, w_down, routing: Routing,
+                       saved: torch.Tensor, want_dtopk_w: bool = True,
+                       ws: torch.Tensor | None = None, opts: MoEOpts | None = None,
+                       out: dict | None = None) -> dict:
+    dev = x.device
+    for t in (dy, x, w_gate, w_up, w_down):
+        assert t.is_cuda and t.dtype == torch.bfloat16 and t.is_contiguous()
+    assert tuple(dy.shape) == (shape.T, shape.d)
+    if out is None:
+        out = {
+            "dx": torch.empty_like(x),
+            "dw_gate": torch.empty_like(w_gate),
+            "dw_up": torch.empty_like(w_up),
+            "dw_down": torch.empty_like(w_down),
+            "dtopk_w": torch.empty((shape.T, shape.k), dtype=torch.float32, device=dev)
+            if want_dtopk_w else None,
+        }
+    if ws is None:
+        ws = _ws(moe_workspace_bytes(shape)["bwd"], dev)
+    cs = routing.c_struct()
+    _check(load_library().moe_fused_backward(
+        ctypes.byref(shape), _ptr(dy), _ptr(x), _ptr(w_gate), _ptr(w_up), _ptr(w_down),
+        ctypes.byref(cs), _ptr(saved), _ptr(out["dx"]), _ptr(out["dw_gate"]), _ptr(out["dw_up"]),
+        _ptr(out["dw_down"]), _ptr(out.get("dtopk_w")), _ptr(ws), ctypes.c_size_t(ws.numel()),
+        ctypes.byref(opts) if opts is not None else None, _stream(dev)), "moe_fused_backward")
+    return out
+
+
+def moe_device_status(ws: torch.Tensor) -> int:
+    return int(load_library().moe_device_status(_ptr(ws), _stream(ws.device)))
+
+
+def alloc_saved(shape: MoEShape, device) -> torch.Tensor:
+    return _ws(moe_workspace_bytes(shape)["saved"], device)
+
+
+def saved_views(shape: MoEShape, saved: torch.Tensor) -> dict:
+    """bf16 views of the stash: gu [A_cap,2I], h [A_cap,I], o [A_cap,d]."""
+    L = moe_saved_layout(shape)
+    A = shape.T * shape.k
+
+    def view(off, cols):
+        return saved[off:off + A * cols * 2].view(torch.bfloat16).view(A, cols)
+
+    return {"gu": view(L["gu"], 2 * shape.I), "h": view(L["h"], shape.I), "o": view(L["o"], shape.d)}

@@ -1,0 +1,199 @@
+// extern "C" boundary: argument checks, workspace carving, launches.
+// Every check happens before anything is enqueued.
+#include "common.hpp"
+
+namespace uniep {
+size_t route_workspace_bytes(const moe_shape_t& s);
+int route_launch(const moe_shape_t& s, const float* logits, const moe_routing_t& out, void* ws,
+                 hipStream_t st);
+size_t fwd_workspace_bytes(const moe_shape_t& s);
+size_t fwd_ctrl_bytes(const moe_shape_t& s);
+int fwd_launch(const moe_shape_t& s, const void* x, const void* w_gate, const void* w_up,
+               const void* w_down, const moe_routing_t& r, void* y, char* gu, char* h, char* o,
+               char* ws, const moe_opts_t& opts, int fm, hipStream_t st);
+size_t bwd_workspace_bytes(const moe_shape_t& s);
+int bwd_launch(const moe_shape_t& s, const void* dy, const void* x, const void* w_gate,
+               const void* w_up, const void* w_down, const moe_routing_t& r, const char* gu,
+               const char* h, const char* o, void* dx, void* dw_gate, void* dw_up, void* dw_down,
+               float* dtopk_w, char* ws, const moe_opts_t& opts, int fm, hipStream_t st);
+}  // namespace uniep
+
+using namespace uniep;
+
+namespace {
+
+int check_shape(const moe_shape_t* s) {
+    if (!s) return MOE_ERR_ARG;
+    if (s->T < 0 || s->d < 64 || s->I < 64 || s->E < 1 || s->k < 1) return MOE_ERR_SHAPE;
+    if (s->k > kMaxTopK || s->E > kMaxExperts || s->k > s->E) return MOE_ERR_SHAPE;
+    if (s->e_start < 0 || s->e_count < 1 || s->e_start + s->e_count > s->E) return MOE_ERR_SHAPE;
+    if (s->d % 64 != 0 || s->I % 64 != 0) return MOE_ERR_SHAPE;
+    if ((int64_t)s->T * s->k >= (1ll << 30)) return MOE_ERR_SHAPE;
+    return MOE_OK;
+}
+
+bool aligned(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
+
+int check_routing(const moe_routing_t* r, int T) {
+    if (!r) return MOE_ERR_ARG;
+    if (!r->counts || !r->offsets) return MOE_ERR_ARG;
+    if (T > 0 && (!r->topk_idx || !r->topk_w || !r->perm || !r->inv_perm)) return MOE_ERR_ARG;
+    if (!aligned(r->topk_idx, 4) || !aligned(r->topk_w, 4) || !aligned(r->counts, 4) ||
+        !aligned(r->offsets, 4) || !aligned(r->perm, 4) || !aligned(r->inv_perm, 4))
+        return MOE_ERR_ARG;
+    return MOE_OK;
+}
+
+int check_opts(const moe_opts_t* o, moe_opts_t* out) {
+    moe_opts_t d = {};
+    if (o) d = *o;
+    if (d.schedule < 0 || d.schedule > 2 || d.workers < 0 || d.spin_limit_ms < 0) return MOE_ERR_ARG;
+    if (d.tile_rows != 0 && d.tile_rows != 128 && d.tile_rows != 256) return MOE_ERR_ARG;
+    for (int i = 0; i < 4; ++i)
+        if (d.reserved[i] != 0) return MOE_ERR_ARG;
+    *out = d;
+    return MOE_OK;
+}
+
+// Row-tile height: 256 rows when experts average several hundred rows, else 128.
+int pick_fm(const moe_shape_t& s, const moe_opts_t& o) {
+    if (o.tile_rows == 128) return 1;
+    if (o.tile_rows == 256) return 2;
+    const double avg = (double)s.T * s.k / s.E;
+    return avg >= 384.0 ? 2 : 1;
+}
+
+struct SavedLayout {
+    size_t gu, h, o, total;
+};
+SavedLayout saved_layout(const moe_shape_t& s) {
+    const size_t A_cap = (size_t)s.T * s.k;
+    SavedLayout L;
+    size_t off = 0;
+    L.gu = off; off = align_up(off + A_cap * 2 * s.I * 2, 256);
+    L.h = off;  off = align_up(off + A_cap * s.I * 2, 256);
+    L.o = off;  off = align_up(off + A_cap * s.d * 2, 256);
+    L.total = off > 0 ? off : 256;
+    return L;
+}
+
+}  // namespace
+
+extern "C" {
+
+int moe_workspace_bytes(const moe_shape_t* shape, size_t* route_ws, size_t* fwd_ws, size_t* bwd_ws,
+                        size_t* saved_bytes) {
+    int rc = check_shape(shape);
+    if (rc != MOE_OK) return rc;
+    if (route_ws) *route_ws = route_workspace_bytes(*shape);
+    if (fwd_ws) *fwd_ws = fwd_workspace_bytes(*shape);
+    if (bwd_ws) *bwd_ws = bwd_workspace_bytes(*shape);
+    if (saved_bytes) *saved_bytes = saved_layout(*shape).total;
+    return MOE_OK;
+}
+
+int moe_saved_layout(const moe_shape_t* shape, size_t* off_gu, size_t* off_h, size_t* off_o) {
+    int rc = check_shape(shape);
+    if (rc != MOE_OK) return rc;
+    const SavedLayout L = saved_layout(*shape);
+    if (off_gu) *off_gu = L.gu;
+    if (off_h) *off_h = L.h;
+    if (off_o) *off_o = L.o;
+    return MOE_OK;
+}
+
+int moe_route(const moe_shape_t* shape, const float* logits, const moe_routing_t* out, void* ws,
+              size_t ws_bytes, void* stream) {
+    int rc = check_shape(shape);
+    if (rc != MOE_OK) return rc;
+    rc = check_routing(out, shape->T);
+    if (rc != MOE_OK) return rc;
+    if (!ws || !aligned(ws, 256)) return MOE_ERR_ARG;
+    if (shape->T > 0 && (!logits || !aligned(logits, 4))) return MOE_ERR_ARG;
+    if (ws_bytes < route_workspace_bytes(*shape)) return MOE_ERR_WORKSPACE;
+    return route_launch(*shape, logits, *out, ws, (hipStream_t)stream);
+}
+
+int moe_fused_forward(const moe_shape_t* shape, const void* x, const void* w_gate, const void* w_up,
+                      const void* w_down, const moe_routing_t* routing, void* y, void* saved,
+                      void* ws, size_t ws_bytes, const moe_opts_t* opts, void* stream) {
+    int rc = check_shape(shape);
+    if (rc != MOE_OK) return rc;
+    rc = check_routing(routing, shape->T);
+    if (rc != MOE_OK) return rc;
+    moe_opts_t o;
+    rc = check_opts(opts, &o);
+    if (rc != MOE_OK) return rc;
+    if (!w_gate || !w_up || !w_down || !ws) return MOE_ERR_ARG;
+    if (shape->T > 0 && (!x || !y)) return MOE_ERR_ARG;
+    if (!aligned(x, 16) || !aligned(y, 16) || !aligned(w_gate, 16) || !aligned(w_up, 16) ||
+        !aligned(w_down, 16) || !aligned(ws, 256) || !aligned(saved, 256))
+        return MOE_ERR_ARG;
+    if (ws_bytes < fwd_workspace_bytes(*shape)) return MOE_ERR_WORKSPACE;
+    if (shape->T == 0) return MOE_OK;
+    char* wsb = (char*)ws;
+    char *gu = nullptr, *h, *ob;
+    if (saved) {
+        const SavedLayout L = saved_layout(*shape);
+        gu = (char*)saved + L.gu;
+        h = (char*)saved + L.h;
+        ob = (char*)saved + L.o;
+    } else {
+        const size_t A_cap = (size_t)shape->T * shape->k;
+        const size_t ctrl = fwd_ctrl_bytes(*shape);
+        h = wsb + ctrl;
+        ob = h + align_up(A_cap * shape->I * 2, 256);
+    }
+    return fwd_launch(*shape, x, w_gate, w_up, w_down, *routing, y, gu, h, ob, wsb, o,
+                      pick_fm(*shape, o), (hipStream_t)stream);
+}
+
+int moe_fused_backward(const moe_shape_t* shape, const void* dy, const void* x, const void* w_gate,
+                       const void* w_up, const void* w_down, const moe_routing_t* routing,
+                       const void* saved, void* dx, void* dw_gate, void* dw_up, void* dw_down,
+                       float* dtopk_w, void* ws, size_t ws_bytes, const moe_opts_t* opts,
+                       void* stream) {
+    int rc = check_shape(shape);
+    if (rc != MOE_OK) return rc;
+    rc = check_routing(routing, shape->T);
+    if (rc != MOE_OK) return rc;
+    moe_opts_t o;
+    rc = check_opts(opts, &o);
+    if (rc != MOE_OK) return rc;
+    if (!w_gate || !w_up || !w_down || !ws || !saved || !dw_gate || !dw_up || !dw_down)
+        return MOE_ERR_ARG;
+    if (shape->T > 0 && (!x || !dy || !dx)) return MOE_ERR_ARG;
+    if (!aligned(x, 16) || !aligned(dy, 16) || !aligned(dx, 16) || !aligned(w_gate, 16) ||
+        !aligned(w_up, 16) || !aligned(w_down, 16) || !aligned(dw_gate, 16) ||
+        !aligned(dw_up, 16) || !aligned(dw_down, 16) || !aligned(ws, 256) ||
+        !aligned(saved, 256) || !aligned(dtopk_w, 4))
+        return MOE_ERR_ARG;
+    if (ws_bytes < bwd_workspace_bytes(*shape)) return MOE_ERR_WORKSPACE;
+    const SavedLayout L = saved_layout(*shape);
+    const char* sv = (const char*)saved;
+    return bwd_launch(*shape, dy, x, w_gate, w_up, w_down, *routing, sv + L.gu, sv + L.h, sv + L.o,
+                      dx, dw_gate, dw_up, dw_down, dtopk_w, (char*)ws, o, pick_fm(*shape, o),
+                      (hipStream_t)stream);
+}
+
+int moe_device_status(const void* ws, void* stream) {
+    if (!ws) return MOE_ERR_ARG;
+    if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return MOE_ERR_HIP;
+    int status = 0;
+    if (hipMemcpy(&status, ws, sizeof(int), hipMemcpyDeviceToHost) != hipSuccess) return MOE_ERR_HIP;
+    return status == 0 ? MOE_OK : MOE_ERR_DEVICE;
+}
+
+const char* moe_status_string(int code) {
+    switch (code) {
+        case MOE_OK: return "ok";
+        case MOE_ERR_ARG: return "bad argument (null or misaligned pointer, bad option)";
+        case MOE_ERR_SHAPE: return "shape outside the supported limits";
+        case MOE_ERR_WORKSPACE: return "workspace or saved buffer too small";
+        case MOE_ERR_HIP: return "HIP runtime call failed";
+        case MOE_ERR_DEVICE: return "a kernel gave up a bounded scoreboard wait";
+        default: return "unknown status";
+    }
+}
+
+}  // extern "C"

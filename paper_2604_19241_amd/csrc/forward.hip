@@ -1,0 +1,390 @@
+// Forward MegaKernel: dispatch(gather) + grouped GEMM gate/up + SwiGLU +
+// grouped GEMM down + combine, as one persistent work-queue kernel.
+//
+// Paper: Section 3.1 (persistent workers, scoreboard, dynamic scheduling),
+// Section 3.2 (GroupGEMM+Combine, top-k accumulation constraint), Section 4.3
+// (producers and consumers walk the experts in the same ascending order),
+// Listing 1 (the fetch loop).  On one GPU the "dispatch" of a token to its
+// expert is a gather: the GEMM1 tile reads the rows of x through the
+// permutation while it stages them into LDS, so the dispatched copy is never
+// written to HBM; the scoreboard that remains orders GEMM1 -> GEMM2 per row
+// tile and GEMM2 -> combine.  SwiGLU runs in the GEMM1 epilogue on the fp32
+// accumulators.
+#include "tiles.hpp"
+
+namespace uniep {
+
+enum TaskType { TASK_GEMM1 = 0, TASK_GEMM2 = 1, TASK_COMBINE = 2 };
+constexpr int kCombineTokens = 16;   // tokens per combine task (4 per wave)
+
+struct FwdParams {
+    moe_shape_t s;
+    const char* x;
+    const char* w_gate;
+    const char* w_up;
+    const char* w_down;
+    const float* topk_w;
+    const int32_t* offsets;
+    const int32_t* perm;
+    const int32_t* inv_perm;
+    char* y;
+    char* gu;   // saved G|U [A,2I] or null
+    char* h;    // [A,I]
+    char* o;    // [A,d]
+    int* ctrl;
+    RowTile* rt;
+    int* flag1;   // per row tile: GEMM1 column tiles finished
+    Task* tasks;
+    int nct1, nct2;   // column tiles of GEMM1 (128 h-columns each) and GEMM2 (256 each)
+    int max_rt;
+    long long spin_ticks;
+};
+
+// ------------------------------------------------------------- prologue
+// One workgroup: row-tile table from the expert offsets, the linearised task
+// list (producers before consumers, experts ascending inside each phase), and
+// a cleared scoreboard.
+template <int BM>
+__global__ void __launch_bounds__(1024) fwd_prologue_kernel(FwdParams p) {
+    __shared__ int32_t s_scan[kMaxExperts];
+    const int e = threadIdx.x;
+    const int ec = p.s.e_count;
+    int cnt = 0, nt = 0;
+    if (e < ec) {
+        cnt = p.offsets[e + 1] - p.offsets[e];
+        nt = (cnt + BM - 1) / BM;
+    }
+    s_scan[e] = nt;
+    __syncthreads();
+    for (int off = 1; off < kMaxExperts; off <<= 1) {
+        const int32_t add = (e >= off) ? s_scan[e - off] : 0;
+        __syncthreads();
+        s_scan[e] += add;
+        __syncthreads();
+    }
+    const int nrt = s_scan[kMaxExperts - 1];
+    if (e < ec) {
+        const int base = s_scan[e] - nt;
+        const int r0 = p.offsets[e];
+        for (int i = 0; i < nt; ++i) {
+            RowTile t;
+            t.expert = e;
+            t.row0 = r0 + i * BM;
+            t.rows = min(BM, cnt - i * BM);
+            t.pad = 0;
+            p.rt[base + i] = t;
+        }
+    }
+    const int n1 = nrt * p.nct1, n2 = nrt * p.nct2;
+    const int n3 = (p.s.T + kCombineTokens - 1) / kCombineTokens;
+    for (int i = e; i < n1; i += 1024) p.tasks[i] = Task{i / p.nct1, (TASK_GEMM1 << 20) | (i % p.nct1)};
+    for (int i = e; i < n2; i += 1024)
+        p.tasks[n1 + i] = Task{i / p.nct2, (TASK_GEMM2 << 20) | (i % p.nct2)};
+    for (int i = e; i < n3; i += 1024) p.tasks[n1 + n2 + i] = Task{i, (TASK_COMBINE << 20)};
+    for (int i = e; i < nrt; i += 1024) p.flag1[i] = 0;
+    if (e < CTRL_WORDS) {
+        int v = 0;
+        if (e == CTRL_NRT) v = nrt;
+        if (e == CTRL_NTASK) v = n1 + n2 + n3;
+        if (e == CTRL_PHASE_END + 0) v = n1;
+        if (e == CTRL_PHASE_END + 1) v = n1 + n2;
+        if (e == CTRL_PHASE_END + 2) v = n1 + n2 + n3;
+        if (e == CTRL_CURSOR + 1 + 1) v = n1;        // phase cursors start at their phase
+        if (e == CTRL_CURSOR + 1 + 2) v = n1 + n2;
+        p.ctrl[e] = v;
+    }
+}
+
+// ------------------------------------------------------------- GEMM1 task
+// h[row0.., ct*128 .. +128) = silu(x_e W_gate) * (x_e W_up) for one row tile.
+// B-tile chunk nb: even -> 8 gate columns, odd -> the same 8 up columns, so the
+// lanes 2q and 2q+1 hold G and U of the same columns.
+template <int FM>
+__device__ __forceinline__ void gemm1_task(const FwdParams& p, const RowTile rt, int ct,
+                                           char* smem) {
+    const int d = p.s.d, I = p.s.I, k = p.s.k;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    RowLoader<4 * FM, false> al;
+    al.init();
+    {
+        const int mrow = tid >> 3, kc = tid & 7;
+#pragma unroll
+        for (int q = 0; q < 4 * FM; ++q) {
+            const int m = min(mrow + 32 * q, rt.rows - 1);   // rows past the tile alias its last row
+            const int tok = p.perm[rt.row0 + m] / k;
+            al.rp[q] = p.x + ((size_t)tok * d + kc * 8) * 2;
+        }
+    }
+    StridedLoader bl;
+    bl.init();
+    const int n0h = ct * (BN / 2);
+    {
+        const int nb = tid & 31, kb = tid >> 5;
+        const int hc = min(n0h + (nb >> 1) * 8, I - 8);   // chunks past I alias the last chunk
+        const char* w = (nb & 1) ? p.w_up : p.w_gate;
+        bl.ld_bytes = (size_t)I * 2;
+        bl.bp = w + (((size_t)rt.expert * d + kb * 8) * I + hc) * 2;
+    }
+    f32x16_t acc[FM][8];
+    mma_mainloop<FM>(al, bl, d / BK, smem, acc);
+
+    // epilogue: SwiGLU on the accumulators; lanes (2q, 2q+1) trade halves so that
+    // each ends with G and U of 4 consecutive h-columns.
+    const int nb = lane & 31;
+    const bool odd = lane & 1;
+    const int hcol = n0h + 4 * nb;              // first of this lane's 4 h-columns
+    const int gcol = n0h + (nb >> 1) * 8;       // first of the 8 G (even) / U (odd) columns
+    const bool col_ok = gcol < I;
+#pragma unroll
+    for (int i = 0; i < FM; ++i) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int m = (wave * FM + i) * 32 + frag_row(v, lane);
+            float hv[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float mine_lo = acc[i][q][v], mine_hi = acc[i][q + 4][v];
+                const float recv = dpp_swap_pair(odd ? mine_lo : mine_hi);
+                const float g = odd ? recv : mine_lo;
+                const float u = odd ? mine_hi : recv;
+                hv[q] = g * sigmoid_f(g) * u;
+            }
+            if (m < rt.rows && col_ok) {
+                const size_t row = (size_t)(rt.row0 + m);
+                u32x2_t hp = {pack_bf16x2(hv[0], hv[1]), pack_bf16x2(hv[2], hv[3])};
+                *(u32x2_t*)(p.h + (row * I + hcol) * 2) = hp;
+                if (p.gu) {
+                    const u32x4_t guv = pack_row8<FM>(acc, i, v);
+                    *(u32x4_t*)(p.gu + (row * 2 * I + (odd ? I : 0) + gcol) * 2) = guv;
+                }
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------- GEMM2 task
+// o[row0.., ct*256 .. +256) = h_e W_down[e] for one row tile.
+template <int FM>
+__device__ __forceinline__ void gemm2_task(const FwdParams& p, const RowTile rt, int ct,
+                                           char* smem) {
+    const int d = p.s.d, I = p.s.I;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    RowLoader<4 * FM, false> al;
+    al.init();
+    {
+        const int mrow = tid >> 3, kc = tid & 7;
+#pragma unroll
+        for (int q = 0; q < 4 * FM; ++q) {
+            const int m = min(mrow + 32 * q, rt.rows - 1);
+            al.rp[q] = p.h + ((size_t)(rt.row0 + m) * I + kc * 8) * 2;
+        }
+    }
+    StridedLoader bl;
+    bl.init();
+    const int n0 = ct * BN;
+    {
+        const int nb = tid & 31, kb = tid >> 5;
+        const int c = min(n0 + nb * 8, d - 8);
+        bl.ld_bytes = (size_t)d * 2;
+        bl.bp = p.w_down + (((size_t)rt.expert * I + kb * 8) * d + c) * 2;
+    }
+    f32x16_t acc[FM][8];
+    mma_mainloop<FM>(al, bl, I / BK, smem, acc);
+    const int col = n0 + (lane & 31) * 8;
+    if (col < d) {
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int m = (wave * FM + i) * 32 + frag_row(v, lane);
+                if (m < rt.rows)
+                    *(u32x4_t*)(p.o + ((size_t)(rt.row0 + m) * d + col) * 2) = pack_row8<FM>(acc, i, v);
+            }
+    }
+}
+
+// ------------------------------------------------------------- combine task
+// y[t] = sum_j w[t,j] * o[row(t,j)], slot order, fp32; one wave per token, 16
+// bytes per lane, no LDS (Section 5.2 "Relay & Reduce Workers").
+__device__ __forceinline__ void combine_task(const FwdParams& p, int block) {
+    const int d = p.s.d, k = p.s.k, T = p.s.T;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int tt = wave; tt < kCombineTokens; tt += 4) {
+        const int t = block * kCombineTokens + tt;
+        if (t >= T) break;
+        int rows[kMaxTopK];
+        float w[kMaxTopK];
+#pragma unroll
+        for (int j = 0; j < kMaxTopK; ++j) {
+            rows[j] = (j < k) ? p.inv_perm[(size_t)t * k + j] : -1;
+            w[j] = (j < k) ? p.topk_w[(size_t)t * k + j] : 0.f;
+        }
+        for (int c = lane * 8; c < d; c += 64 * 8) {
+            float a[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) a[q] = 0.f;
+#pragma unroll
+            for (int j = 0; j < kMaxTopK; ++j) {
+                if (j < k && rows[j] >= 0) {
+                    const u32x4_t ov = *(const u32x4_t*)(p.o + ((size_t)rows[j] * d + c) * 2);
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        a[2 * q] += w[j] * bf16_lo(ov[q]);
+                        a[2 * q + 1] += w[j] * bf16_hi(ov[q]);
+                    }
+                }
+            }
+            u32x4_t yv;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) yv[q] = pack_bf16x2(a[2 * q], a[2 * q + 1]);
+            *(u32x4_t*)(p.y + ((size_t)t * d + c) * 2) = yv;
+        }
+    }
+}
+
+// ------------------------------------------------------------- the worker loop
+// phase < 0: the whole queue with scoreboard waits (persistent MegaKernel).
+// phase >= 0: only that phase's tasks (staged schedule; the waits are already
+// satisfied by stream order).
+template <int FM>
+__global__ void __launch_bounds__(kTileThreads) fwd_worker_kernel(FwdParams p, int phase) {
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    __shared__ int s_task;
+    __shared__ int s_ok;
+    int* ctrl = p.ctrl;
+    const int end = (phase < 0) ? ctrl[CTRL_NTASK] : ctrl[CTRL_PHASE_END + phase];
+    int* cursor = ctrl + CTRL_CURSOR + (phase < 0 ? 0 : 1 + phase);
+    const int n2_total = ctrl[CTRL_PHASE_END + 1] - ctrl[CTRL_PHASE_END + 0];
+    for (;;) {
+        if (threadIdx.x == 0) s_task = atomicAdd(cursor, 1);
+        __syncthreads();
+        const int id = s_task;
+        if (id >= end) break;
+        const Task task = p.tasks[id];
+        const int type = task.type_ct >> 20, ct = task.type_ct & 0xfffff;
+        if (type == TASK_GEMM1) {
+            const RowTile rt = p.rt[task.rt];
+            gemm1_task<FM>(p, rt, ct, smem);
+            __syncthreads();   // all h stores of the tile issued and complete at workgroup scope
+            if (threadIdx.x == 0) add_release(p.flag1 + task.rt, 1);
+        } else if (type == TASK_GEMM2) {
+            if (threadIdx.x == 0) s_ok = wait_ge(p.flag1 + task.rt, p.nct1, ctrl, p.spin_ticks);
+            __syncthreads();
+            if (s_ok) {
+                const RowTile rt = p.rt[task.rt];
+                gemm2_task<FM>(p, rt, ct, smem);
+            }
+            __syncthreads();
+            if (threadIdx.x == 0) add_release(ctrl + CTRL_DONE + 1, 1);
+        } else {
+            if (threadIdx.x == 0) s_ok = wait_ge(ctrl + CTRL_DONE + 1, n2_total, ctrl, p.spin_ticks);
+            __syncthreads();
+            if (s_ok) combine_task(p, task.rt);
+        }
+        __syncthreads();   // s_task / s_ok are rewritten next round
+    }
+}
+
+// ------------------------------------------------------------------ host side
+
+struct FwdLayout {
+    size_t ctrl, rt, flag1, tasks, h, o, total;
+    int max_rt, nct1, nct2;
+    size_t max_tasks;
+};
+
+FwdLayout fwd_layout(const moe_shape_t& s, bool with_ho) {
+    FwdLayout L;
+    const size_t A_cap = (size_t)s.T * s.k;
+    L.max_rt = (int)((A_cap + 127) / 128) + s.e_count;
+    L.nct1 = (s.I + BN / 2 - 1) / (BN / 2);
+    L.nct2 = (s.d + BN - 1) / BN;
+    L.max_tasks = (size_t)L.max_rt * (L.nct1 + L.nct2) + (s.T + kCombineTokens - 1) / kCombineTokens;
+    size_t off = 0;
+    L.ctrl = off;  off = align_up(off + CTRL_WORDS * sizeof(int), 256);
+    L.rt = off;    off = align_up(off + (size_t)L.max_rt * sizeof(RowTile), 256);
+    L.flag1 = off; off = align_up(off + (size_t)L.max_rt * sizeof(int), 256);
+    L.tasks = off; off = align_up(off + L.max_tasks * sizeof(Task), 256);
+    L.h = off;     if (with_ho) off = align_up(off + A_cap * s.I * 2, 256);
+    L.o = off;     if (with_ho) off = align_up(off + A_cap * s.d * 2, 256);
+    L.total = off;
+    return L;
+}
+
+size_t fwd_workspace_bytes(const moe_shape_t& s) { return fwd_layout(s, true).total; }
+size_t fwd_ctrl_bytes(const moe_shape_t& s) { return fwd_layout(s, false).total; }
+
+static int g_workers[16];   // resident worker slots per device, per FM (index dev*2 + FM-1)
+
+template <int FM>
+static int resident_workers(int* out) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return MOE_ERR_HIP;
+    const int slot = (dev & 7) * 2 + (FM - 1);
+    if (g_workers[slot] == 0) {
+        if (hipFuncSetAttribute((const void*)fwd_worker_kernel<FM>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize,
+                                Geom<FM>::SMEM) != hipSuccess)
+            return MOE_ERR_HIP;
+        int per_cu = 0, cus = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fwd_worker_kernel<FM>,
+                                                         kTileThreads, Geom<FM>::SMEM) != hipSuccess)
+            return MOE_ERR_HIP;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+            return MOE_ERR_HIP;
+        if (per_cu < 1 || cus < 1) return MOE_ERR_HIP;
+        g_workers[slot] = per_cu * cus;
+    }
+    *out = g_workers[slot];
+    return MOE_OK;
+}
+
+template <int FM>
+static int fwd_launch_fm(FwdParams& p, const moe_opts_t& opts, hipStream_t st) {
+    int resident = 0;
+    int rc = resident_workers<FM>(&resident);
+    if (rc != MOE_OK) return rc;
+    int workers = opts.workers > 0 ? min(opts.workers, resident) : resident;
+    hipLaunchKernelGGL(fwd_prologue_kernel<Geom<FM>::BM>, dim3(1), dim3(1024), 0, st, p);
+    if (opts.schedule == 2) {
+        for (int phase = 0; phase < 3; ++phase)
+            hipLaunchKernelGGL(fwd_worker_kernel<FM>, dim3(workers), dim3(kTileThreads),
+                               Geom<FM>::SMEM, st, p, phase);
+    } else {
+        hipLaunchKernelGGL(fwd_worker_kernel<FM>, dim3(workers), dim3(kTileThreads),
+                           Geom<FM>::SMEM, st, p, -1);
+    }
+    return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
+}
+
+int fwd_launch(const moe_shape_t& s, const void* x, const void* w_gate, const void* w_up,
+               const void* w_down, const moe_routing_t& r, void* y, char* gu, char* h, char* o,
+               char* ws, const moe_opts_t& opts, int fm, hipStream_t st) {
+    const FwdLayout L = fwd_layout(s, false);
+    FwdParams p;
+    p.s = s;
+    p.x = (const char*)x;
+    p.w_gate = (const char*)w_gate;
+    p.w_up = (const char*)w_up;
+    p.w_down = (const char*)w_down;
+    p.topk_w = r.topk_w;
+    p.offsets = r.offsets;
+    p.perm = r.perm;
+    p.inv_perm = r.inv_perm;
+    p.y = (char*)y;
+    p.gu = gu;
+    p.h = h;
+    p.o = o;
+    p.ctrl = (int*)(ws + L.ctrl);
+    p.rt = (RowTile*)(ws + L.rt);
+    p.flag1 = (int*)(ws + L.flag1);
+    p.tasks = (Task*)(ws + L.tasks);
+    p.nct1 = L.nct1;
+    p.nct2 = L.nct2;
+    p.max_rt = L.max_rt;
+    const int ms = opts.spin_limit_ms > 0 ? opts.spin_limit_ms : 2000;
+    p.spin_ticks = (long long)ms * 100000ll;   // wall_clock64 ticks at 100 MHz
+    return fm == 1 ? fwd_launch_fm<1>(p, opts, st) : fwd_launch_fm<2>(p, opts, st);
+}
+
+}  // namespace uniep

@@ -1,0 +1,232 @@
+// Routing and deterministic token mapping on one GPU.
+//
+// Paper: Section 2.1 (gating, top-k), Section 3.1 "Deterministic Token Mapping",
+// Algorithm 1 lines 1-2 (BinCount, CumSum) and the local stable order M_loc; with
+// one rank the global offset base is zero, so the destination row of a
+// (token, slot) pair is  offsets[e] + rank of the pair among the pairs of e.
+//
+// No position is ever handed out by an atomic: the flat slots are cut into
+// fixed chunks, each chunk counts its experts, a scan over chunks gives every
+// chunk its starting row per expert, and inside a chunk ranks come from wave
+// ballots in lane order.  The result is therefore the same on every run.
+#include "common.hpp"
+
+namespace uniep {
+
+constexpr int kChunk = 256;        // flat slots per wave-chunk (4 wave iterations)
+constexpr int kRouteThreads = 256; // 4 waves per workgroup
+
+// ---------------------------------------------------------------- top-k + gates
+// One wave per token.  Lane l holds experts l, l+64, ...  k rounds of arg-max
+// under the order (value desc, expert id asc); gates from the k selected logits
+// (the softmax denominator over all E cancels in the renormalisation).
+template <int EPL>
+__global__ void __launch_bounds__(kRouteThreads)
+topk_gate_kernel(const float* __restrict__ logits, int T, int E, int k,
+                 int32_t* __restrict__ topk_idx, float* __restrict__ topk_w) {
+    const int lane = threadIdx.x & 63;
+    const int t = blockIdx.x * (kRouteThreads / 64) + (threadIdx.x >> 6);
+    if (t >= T) return;
+    const float* row = logits + (size_t)t * E;
+    float v[EPL];
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) {
+        const int e = lane + 64 * i;
+        v[i] = (e < E) ? row[e] : -INFINITY;
+    }
+    uint32_t taken = 0;
+#pragma unroll
+    for (int i = 0; i < EPL; ++i)
+        if (lane + 64 * i >= E) taken |= 1u << i;   // padding lanes never win
+    float my_val = 0.f;
+    int my_idx = 0;
+    float top1 = 0.f;
+    for (int j = 0; j < k; ++j) {
+        float bv = -INFINITY;
+        int be = 0x7fffffff;
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) {
+            const int e = lane + 64 * i;
+            const bool free_ = !((taken >> i) & 1u);
+            if (free_ && (v[i] > bv || (v[i] == bv && e < be))) { bv = v[i]; be = e; }
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            const float ov = __shfl_xor(bv, off);
+            const int oe = __shfl_xor(be, off);
+            if (ov > bv || (ov == bv && oe < be)) { bv = ov; be = oe; }
+        }
+        // every lane now agrees on (bv, be); the owner retires it
+        if ((be & 63) == lane) taken |= 1u << (be >> 6);
+        if (j == 0) top1 = bv;
+        if (lane == j) { my_val = bv; my_idx = be; }
+    }
+    float p = (lane < k) ? __expf(my_val - top1) : 0.f;
+    float s = p;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) s += __shfl_xor(s, off);
+    if (lane < k) {
+        topk_idx[(size_t)t * k + lane] = my_idx;
+        topk_w[(size_t)t * k + lane] = p / s;
+    }
+}
+
+// ------------------------------------------------------- per-chunk BinCount
+// chunk_cnt[c][e] = number of slots of chunk c routed to local expert e.
+// Also pre-fills perm with -1 (rows at and beyond A keep it).
+__global__ void __launch_bounds__(kRouteThreads)
+chunk_count_kernel(const int32_t* __restrict__ topk_idx, int F, int e_start, int e_count,
+                   int32_t* __restrict__ chunk_cnt, int32_t* __restrict__ perm) {
+    extern __shared__ int32_t s_cnt[];   // [4][e_count]
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int chunk = blockIdx.x * (kRouteThreads / 64) + wave;
+    int32_t* cnt = s_cnt + wave * e_count;
+    for (int e = lane; e < e_count; e += 64) cnt[e] = 0;
+    __syncthreads();
+    const int f0 = chunk * kChunk;
+    for (int it = 0; it < kChunk / 64; ++it) {
+        const int f = f0 + it * 64 + lane;
+        if (f < F) {
+            perm[f] = -1;
+            const int el = topk_idx[f] - e_start;
+            if (el >= 0 && el < e_count) atomicAdd(&cnt[el], 1);   // integer sum: order-free
+        }
+    }
+    __syncthreads();
+    if (f0 < F)
+        for (int e = lane; e < e_count; e += 64) chunk_cnt[(size_t)chunk * e_count + e] = cnt[e];
+}
+
+// ------------------------------------------- scan over chunks, then over experts
+// One workgroup.  In place: chunk_cnt[c][e] becomes the number of e-slots in
+// chunks before c.  counts[e] = total, offsets = exclusive CumSum(counts).
+__global__ void __launch_bounds__(1024)
+scan_kernel(int32_t* __restrict__ chunk_cnt, int n_chunks, int e_count,
+            int32_t* __restrict__ counts, int32_t* __restrict__ offsets) {
+    __shared__ int32_t s_tot[kMaxExperts];
+    const int e = threadIdx.x;
+    int32_t run = 0;
+    if (e < e_count) {
+        int c = 0;
+        for (; c + 8 <= n_chunks; c += 8) {
+            int32_t tmp[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) tmp[u] = chunk_cnt[(size_t)(c + u) * e_count + e];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                chunk_cnt[(size_t)(c + u) * e_count + e] = run;
+                run += tmp[u];
+            }
+        }
+        for (; c < n_chunks; ++c) {
+            const int32_t tmp = chunk_cnt[(size_t)c * e_count + e];
+            chunk_cnt[(size_t)c * e_count + e] = run;
+            run += tmp;
+        }
+        counts[e] = run;
+    }
+    s_tot[e] = (e < e_count) ? run : 0;
+    __syncthreads();
+    // inclusive Hillis-Steele scan over 1024 entries
+    for (int off = 1; off < kMaxExperts; off <<= 1) {
+        const int32_t add = (e >= off) ? s_tot[e - off] : 0;
+        __syncthreads();
+        s_tot[e] += add;
+        __syncthreads();
+    }
+    if (e < e_count) offsets[e + 1] = s_tot[e];
+    if (e == 0) offsets[0] = 0;
+}
+
+// ------------------------------------------------------------ stable positions
+// Each wave walks its chunk 64 slots at a time.  cur[e] = next free row of
+// expert e for this chunk; lanes that share an expert take consecutive rows in
+// lane order (= flat-slot order), found with a ballot per distinct expert.
+__global__ void __launch_bounds__(kRouteThreads)
+position_kernel(const int32_t* __restrict__ topk_idx, int F, int e_start, int e_count,
+                const int32_t* __restrict__ chunk_base, const int32_t* __restrict__ offsets,
+                int32_t* __restrict__ perm, int32_t* __restrict__ inv_perm) {
+    extern __shared__ int32_t s_cur_all[];   // [4][e_count]
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int chunk = blockIdx.x * (kRouteThreads / 64) + wave;
+    volatile int32_t* cur = s_cur_all + wave * e_count;
+    const int f0 = chunk * kChunk;
+    if (f0 >= F) return;   // whole wave leaves together; no workgroup barrier below
+    for (int e = lane; e < e_count; e += 64)
+        cur[e] = offsets[e] + chunk_base[(size_t)chunk * e_count + e];
+    __builtin_amdgcn_wave_barrier();
+    const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+    for (int it = 0; it < kChunk / 64; ++it) {
+        const int f = f0 + it * 64 + lane;
+        int el = -1;
+        if (f < F) {
+            el = topk_idx[f] - e_start;
+            if (el < 0 || el >= e_count) el = -1;
+        }
+        int row = -1;
+        uint64_t remaining = __ballot(el >= 0);
+        while (remaining) {
+            const int leader = __builtin_ctzll(remaining);
+            const int e0 = __shfl(el, leader);
+            const uint64_t m = __ballot(el == e0);
+            const int base = cur[e0];
+            __builtin_amdgcn_wave_barrier();
+            if (el == e0) row = base + __popcll(m & lt_mask);
+            if (lane == leader) cur[e0] = base + __popcll(m);
+            __builtin_amdgcn_wave_barrier();
+            remaining &= ~m;
+        }
+        if (f < F) {
+            inv_perm[f] = row;
+            if (row >= 0) perm[row] = f;
+        }
+    }
+}
+
+// ------------------------------------------------------------------ host side
+
+size_t route_workspace_bytes(const moe_shape_t& s) {
+    const size_t F = (size_t)s.T * s.k;
+    const size_t n_chunks = (F + kChunk - 1) / kChunk;
+    return align_up(n_chunks * (size_t)s.e_count * sizeof(int32_t) + 256, 256);
+}
+
+template <int EPL>
+static void launch_topk(const moe_shape_t& s, const float* logits, int32_t* idx, float* w,
+                        hipStream_t st) {
+    const int per = kRouteThreads / 64;
+    hipLaunchKernelGGL(topk_gate_kernel<EPL>, dim3((s.T + per - 1) / per), dim3(kRouteThreads), 0,
+                       st, logits, s.T, s.E, s.k, idx, w);
+}
+
+int route_launch(const moe_shape_t& s, const float* logits, const moe_routing_t& out, void* ws,
+                 hipStream_t st) {
+    int32_t* chunk_cnt = (int32_t*)ws;
+    const int F = s.T * s.k;
+    const int n_chunks = (F + kChunk - 1) / kChunk;
+    if (s.T > 0) {
+        const int epl = (s.E + 63) / 64;
+        if (epl <= 1) launch_topk<1>(s, logits, (int32_t*)out.topk_idx, (float*)out.topk_w, st);
+        else if (epl <= 2) launch_topk<2>(s, logits, (int32_t*)out.topk_idx, (float*)out.topk_w, st);
+        else if (epl <= 4) launch_topk<4>(s, logits, (int32_t*)out.topk_idx, (float*)out.topk_w, st);
+        else if (epl <= 8) launch_topk<8>(s, logits, (int32_t*)out.topk_idx, (float*)out.topk_w, st);
+        else launch_topk<16>(s, logits, (int32_t*)out.topk_idx, (float*)out.topk_w, st);
+        const int per = kRouteThreads / 64;
+        const size_t sm = (size_t)per * s.e_count * sizeof(int32_t);
+        hipLaunchKernelGGL(chunk_count_kernel, dim3((n_chunks + per - 1) / per),
+                           dim3(kRouteThreads), sm, st, out.topk_idx, F, s.e_start, s.e_count,
+                           chunk_cnt, (int32_t*)out.perm);
+    }
+    hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(1024), 0, st, chunk_cnt, n_chunks, s.e_count,
+                       (int32_t*)out.counts, (int32_t*)out.offsets);
+    if (s.T > 0) {
+        const int per = kRouteThreads / 64;
+        const size_t sm = (size_t)per * s.e_count * sizeof(int32_t);
+        hipLaunchKernelGGL(position_kernel, dim3((n_chunks + per - 1) / per), dim3(kRouteThreads),
+                           sm, st, out.topk_idx, F, s.e_start, s.e_count, chunk_cnt, out.offsets,
+                           (int32_t*)out.perm, (int32_t*)out.inv_perm);
+    }
+    return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
+}
+
+}  // namespace uniep

@@ -1,0 +1,115 @@
+"""Host-only checks of the C-ABI library: it loads, exports every symbol the
+header declares, and rejects bad arguments before touching a device."""
+import ctypes
+import re
+from pathlib import Path
+
+import pytest
+
+ROOT = Path(__file__).resolve().parents[1]
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2604_19241_amd import binding
+    if not binding.LIB_PATH.exists():
+        from paper_2604_19241_amd import build
+        build.build()
+    return binding.load_library()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    header = (ROOT / "include" / "uniep_moe.h").read_text()
+    names = set(re.findall(r"^(?:int|const char\*)\s+(moe_\w+)\s*\(", header, flags=re.M))
+    assert {"moe_route", "moe_fused_forward", "moe_fused_backward", "moe_workspace_bytes",
+            "moe_saved_layout", "moe_device_status", "moe_status_string"} <= names
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_status_strings(lib):
+    from paper_2604_19241_amd import binding as b
+    for code in (0, -1, -2, -3, -4, -5):
+        assert b.status_string(code)
+    assert b.status_string(-99) == "unknown status"
+
+
+def test_struct_sizes_match_header(lib):
+    from paper_2604_19241_amd import binding as b
+    assert ctypes.sizeof(b.MoEShape) == 28
+    assert ctypes.sizeof(b.MoEOpts) == 32
+    assert ctypes.sizeof(b.MoERoutingC) == 48
+
+
+@pytest.mark.parametrize("kw", [
+    dict(T=8, d=100, E=8, k=2, I=64),        # d not a multiple of 64
+    dict(T=8, d=64, E=8, k=2, I=96),         # I not a multiple of 64
+    dict(T=8, d=64, E=4, k=5, I=64),         # k > E
+    dict(T=8, d=64, E=8, k=17, I=64),        # k > 16
+    dict(T=8, d=64, E=2048, k=2, I=64),      # E > 1024
+    dict(T=8, d=64, E=8, k=2, I=64, e_start=6, e_count=3),   # window past E
+    dict(T=8, d=64, E=8, k=2, I=64, e_start=0, e_count=0),
+    dict(T=-1, d=64, E=8, k=2, I=64),
+])
+def test_bad_shapes_are_rejected(lib, kw):
+    from paper_2604_19241_amd import binding as b
+    s = b.make_shape(**kw)
+    sizes = [ctypes.c_size_t(0) for _ in range(4)]
+    rc = lib.moe_workspace_bytes(ctypes.byref(s), *[ctypes.byref(v) for v in sizes])
+    assert rc == b.MOE_ERR_SHAPE
+    rc = lib.moe_route(ctypes.byref(s), None, None, None, ctypes.c_size_t(0), None)
+    assert rc == b.MOE_ERR_SHAPE
+
+
+def test_workspace_sizes_and_layout(lib):
+    from paper_2604_19241_amd import binding as b
+    s = b.make_shape(T=256, d=512, E=8, k=2, I=1024)
+    w = b.moe_workspace_bytes(s)
+    A = 256 * 2
+    assert w["saved"] >= A * (2 * 1024 + 1024 + 512) * 2
+    assert w["fwd"] >= A * (1024 + 512) * 2
+    assert w["route"] >= 256 and w["bwd"] >= 256
+    L = b.moe_saved_layout(s)
+    assert L["gu"] == 0 and L["h"] >= A * 2048 * 2 and L["o"] >= L["h"] + A * 1024 * 2
+    assert all(v % 256 == 0 for v in L.values())
+
+
+def test_null_and_misaligned_pointers_are_rejected_before_any_launch(lib):
+    from paper_2604_19241_amd import binding as b
+    s = b.make_shape(T=8, d=64, E=8, k=2, I=64)
+    fake = ctypes.c_void_p(0x1000)            # never dereferenced: checks come first
+    r_ok = b.MoERoutingC(*([0x1000] * 6))
+    r_null = b.MoERoutingC(0x1000, 0, 0x1000, 0x1000, 0x1000, 0x1000)
+    big = ctypes.c_size_t(1 << 40)
+    # routing struct with a null member
+    assert lib.moe_route(ctypes.byref(s), fake, ctypes.byref(r_null), fake, big, None) == b.MOE_ERR_ARG
+    # workspace too small
+    assert lib.moe_route(ctypes.byref(s), fake, ctypes.byref(r_ok), fake, ctypes.c_size_t(8), None) \
+        == b.MOE_ERR_WORKSPACE
+    # forward: null weights, misaligned x, small workspace, bad option
+    args = dict(x=fake, wg=fake, wu=fake, wd=fake, y=fake, saved=None, ws=fake)
+
+    def fwd(x=fake, wg=fake, wu=fake, wd=fake, y=fake, saved=None, ws=fake, nbytes=big, opts=None):
+        return lib.moe_fused_forward(ctypes.byref(s), x, wg, wu, wd, ctypes.byref(r_ok), y, saved,
+                                     ws, nbytes, opts, None)
+
+    assert fwd(wg=None) == b.MOE_ERR_ARG
+    assert fwd(x=ctypes.c_void_p(0x1002)) == b.MOE_ERR_ARG
+    assert fwd(ws=ctypes.c_void_p(0x1010)) == b.MOE_ERR_ARG
+    assert fwd(nbytes=ctypes.c_size_t(16)) == b.MOE_ERR_WORKSPACE
+    bad = b.make_opts(schedule=7)
+    assert fwd(opts=ctypes.byref(bad)) == b.MOE_ERR_ARG
+    bad = b.make_opts(tile_rows=64)
+    assert fwd(opts=ctypes.byref(bad)) == b.MOE_ERR_ARG
+    # backward needs the stash
+    rc = lib.moe_fused_backward(ctypes.byref(s), fake, fake, fake, fake, fake, ctypes.byref(r_ok),
+                                None, fake, fake, fake, fake, None, fake, big, None, None)
+    assert rc == b.MOE_ERR_ARG
+
+
+def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
+    from paper_2604_19241_amd import binding as b
+    monkeypatch.setattr(b, "_lib", None)
+    monkeypatch.setattr(b, "LIB_PATH", tmp_path / "nope.so")
+    with pytest.raises(FileNotFoundError):
+        b.load_library()

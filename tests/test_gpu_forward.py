@@ -1,0 +1,120 @@
+"""GPU parity of moe_fused_forward against the oracle, element by element on
+sizes that span several tiles with ragged tails, for both schedules and both
+row-tile heights; stage outputs (G, U, h, o) through the stash; determinism."""
+import numpy as np
+import pytest
+import torch
+
+import moe_synth
+import oracle
+from helpers import bits, gpu_routing_as_np, max_abs, rel_l2, say, scaled_inputs, to_f64
+
+pytestmark = pytest.mark.gpu
+
+# the benchmark spec tolerances (bf16 forward)
+MAX_ABS = 2e-2
+REL_L2 = 5e-3
+
+
+def gpu_forward(cfg, inp, schedule, tile_rows, with_saved=True, workers=0):
+    import paper_2604_19241_amd as moe
+    shape = moe.make_shape(**cfg.shape_dict())
+    dev = {key: v.cuda() for key, v in inp.items()}
+    routing = moe.moe_route(shape, dev["logits"])
+    saved = moe.alloc_saved(shape, "cuda") if with_saved else None
+    ws = torch.empty(moe.moe_workspace_bytes(shape)["fwd"], dtype=torch.uint8, device="cuda")
+    opts = moe.make_opts(schedule=schedule, tile_rows=tile_rows, workers=workers,
+                         spin_limit_ms=500)
+    y = moe.moe_fused_forward(shape, dev["x"], dev["w_gate"], dev["w_up"], dev["w_down"], routing,
+                              saved=saved, ws=ws, opts=opts)
+    assert moe.moe_device_status(ws) == 0
+    views = moe.saved_views(shape, saved) if with_saved else None
+    return y, routing, views
+
+
+def check_forward(cfg, seed, schedule, tile_rows, wscale=1.0):
+    say(f"[fwd] {cfg.shape_dict()} schedule={schedule} tile_rows={tile_rows} wscale={wscale}")
+    inp = scaled_inputs(cfg, seed, wscale)
+    b = bits(inp, ("x", "w_gate", "w_up", "w_down"))
+    r = oracle.route(cfg.shape_dict(), inp["logits"].numpy())
+    y, routing, views = gpu_forward(cfg, inp, schedule, tile_rows)
+    g = gpu_routing_as_np(routing)
+    for key in ("topk_idx", "counts", "offsets", "perm", "inv_perm"):
+        assert np.array_equal(g[key], r[key]), key
+    A = int(r["offsets"][-1])
+    for acc in ("f64", "f32"):
+        want = oracle.forward(cfg.shape_dict(), b["x"], b["w_gate"], b["w_up"], b["w_down"], r,
+                              round_bf16=True, acc=acc, stages=True)
+        yg = to_f64(y)
+        e_abs, e_rel = max_abs(yg, want["y"]), rel_l2(yg, want["y"])
+        say(f"   vs oracle[{acc}]: y max_abs={e_abs:.3e} rel_l2={e_rel:.3e}")
+        assert e_abs <= MAX_ABS and e_rel <= REL_L2
+        if A > 0:
+            gu = to_f64(views["gu"][:A])
+            assert rel_l2(gu[:, :cfg.I], want["G"]) <= REL_L2, "G"
+            assert rel_l2(gu[:, cfg.I:], want["U"]) <= REL_L2, "U"
+            assert rel_l2(to_f64(views["h"][:A]), want["h"]) <= REL_L2, "h"
+            assert rel_l2(to_f64(views["o"][:A]), want["o"]) <= REL_L2, "o"
+    return y
+
+
+SMALL = [
+    # several row tiles per expert, ragged rows; I = 320 leaves a ragged GEMM1 column tile,
+    # d = 320 a ragged GEMM2 column tile
+    dict(T=700, d=320, E=4, k=2, I=320),
+    dict(T=256, d=512, E=8, k=2, I=1024),                       # config 0
+    dict(T=300, d=256, E=16, k=4, I=192, e_start=4, e_count=8),  # expert window
+    dict(T=97, d=128, E=32, k=8, I=64),                         # few rows per expert
+]
+
+
+@pytest.mark.parametrize("kw", SMALL)
+@pytest.mark.parametrize("schedule", [2, 1])
+@pytest.mark.parametrize("tile_rows", [128, 256])
+def test_forward_matches_oracle(kw, schedule, tile_rows):
+    cfg = moe_synth.small_config(**kw)
+    check_forward(cfg, seed=11, schedule=schedule, tile_rows=tile_rows, wscale=4.0)
+
+
+def test_forward_config0_default_options():
+    cfg = moe_synth.CONFIGS[0]
+    check_forward(cfg, seed=None, schedule=0, tile_rows=0)
+
+
+def test_forward_degenerate_routing():
+    # every token to one expert; and experts that receive nothing
+    cfg = moe_synth.small_config(T=300, d=128, E=6, k=1, I=128)
+    inp = scaled_inputs(cfg, 3, 4.0)
+    inp["logits"][:, :] = 0.0
+    inp["logits"][:, 4] = 3.0
+    b = bits(inp, ("x", "w_gate", "w_up", "w_down"))
+    r = oracle.route(cfg.shape_dict(), inp["logits"].numpy())
+    want = oracle.forward(cfg.shape_dict(), b["x"], b["w_gate"], b["w_up"], b["w_down"], r)["y"]
+    for schedule in (2, 1):
+        say(f"[fwd] one-expert schedule={schedule}")
+        y, _, _ = gpu_forward(cfg, inp, schedule, 0)
+        assert rel_l2(to_f64(y), want) <= REL_L2
+    # no token is local: y must be exactly zero
+    cfg2 = moe_synth.small_config(T=64, d=128, E=8, k=1, I=128, e_start=6, e_count=2)
+    inp2 = scaled_inputs(cfg2, 4, 4.0)
+    inp2["logits"][:, :] = 0.0
+    inp2["logits"][:, 1] = 3.0
+    say("[fwd] nothing local")
+    y2, routing2, _ = gpu_forward(cfg2, inp2, 1, 0)
+    assert int(routing2.offsets[-1]) == 0
+    assert (y2 == 0).all()
+
+
+def test_forward_is_bitwise_repeatable_and_schedule_independent():
+    cfg = moe_synth.small_config(T=900, d=256, E=16, k=4, I=256, zipf_s=1.2)
+    inp = scaled_inputs(cfg, 21, 4.0)
+    say("[fwd] determinism 10 runs, persistent")
+    first, _, _ = gpu_forward(cfg, inp, 1, 0, with_saved=False)
+    ref = first.clone()
+    for i in range(9):
+        again, _, _ = gpu_forward(cfg, inp, 1, 0, with_saved=False)
+        assert torch.equal(ref, again), f"run {i + 1} differs"
+    say("[fwd] determinism across schedules, worker counts and tile heights")
+    for schedule, workers, tile_rows in ((2, 0, 0), (1, 7, 0), (1, 64, 0), (1, 0, 128), (1, 0, 256)):
+        other, _, _ = gpu_forward(cfg, inp, schedule, tile_rows, with_saved=False, workers=workers)
+        assert torch.equal(ref, other), (schedule, workers, tile_rows)
