@@ -1,0 +1,211 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused MoE hot path on one MI355X.
+
+One step = one pass of the whole path over one synthetic batch that is already
+resident in HBM: moe_route -> moe_fused_forward -> moe_fused_backward (when the
+workload has a backward).  Prints ONE JSON line:
+
+  value       useful TFLOP/s of the whole step (6*A*d*I forward + 12*A*d*I
+              backward, A = realised routed rows) -- the metric the benchmark spec names
+  roofline    the forward MegaKernel against the bf16 dense MFMA peak
+  cpu_baseline  the CPU oracle timed on a bounded sample of the same workload
+
+Usage: python bench.py [--gpus 1] [--steps K] [--warmup W] [--config N]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+from pathlib import Path
+
+ROOT = Path(__file__).resolve().parent
+if str(ROOT) not in sys.path:
+    sys.path.insert(0, str(ROOT))
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 matrix peak (published)
+HBM_PEAK_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", type=int, default=2, help="index into BASELINE.json configs")
+    ap.add_argument("--schedule", type=int, default=0)
+    ap.add_argument("--tile-rows", type=int, default=0)
+    ap.add_argument("--workers", type=int, default=0)
+    ap.add_argument("--no-backward", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    return ap.parse_args()
+
+
+def event_ms(fn, n):
+    """Average milliseconds of fn() over n calls, HIP events on torch's current stream
+    (the stream the library launches on)."""
+    import torch
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+           for _ in range(n)]
+    for a, b in evs:
+        a.record()
+        fn()
+        b.record()
+    torch.cuda.synchronize()
+    ts = sorted(a.elapsed_time(b) for a, b in evs)
+    return sum(ts) / len(ts), ts[len(ts) // 2], ts[0]
+
+
+def cpu_baseline(cfg, inp, has_bwd, budget_s):
+    """The oracle as it stands, on the rows of the first S local experts (same inputs)."""
+    import numpy as np
+    import moe_synth
+    import oracle
+    sh_full = cfg.shape_dict()
+    logits = inp["logits"].numpy()
+
+    def run(S):
+        sh = dict(sh_full, e_start=cfg.e_start, e_count=S)
+        b = {k: oracle.bf16_bits(inp[k][:S] if k.startswith("w_") else inp[k])
+             for k in ("x", "w_gate", "w_up", "w_down") + (("dy",) if has_bwd else ())}
+        t0 = time.perf_counter()
+        r = oracle.route(sh, logits, acc="f32")
+        oracle.forward(sh, b["x"], b["w_gate"], b["w_up"], b["w_down"], r, acc="f32")
+        if has_bwd:
+            oracle.backward(sh, b["x"], b["dy"], b["w_gate"], b["w_up"], b["w_down"], r, acc="f32")
+        dt = time.perf_counter() - t0
+        rows = int(r["offsets"][-1])
+        return dt, rows
+
+    dt1, rows1 = run(1)
+    per_expert = max(dt1, 1e-3)
+    S = int(max(1, min(cfg.e_count, budget_s / per_expert)))
+    dt, rows = (dt1, rows1) if S == 1 else run(S)
+    flops = (18 if has_bwd else 6) * rows * cfg.d * cfg.I
+    return {
+        "value": flops / dt / 1e12,
+        "unit": "TFLOP/s",
+        "cores": oracle.threads(),
+        "kind": "oracle",
+        "sample": f"rows of the first {S} of {cfg.e_count} local experts ({rows} of the routed rows), "
+                  f"route+forward{'+backward' if has_bwd else ''}, fp32 accumulate, {dt:.1f} s",
+    }
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import moe_synth
+    import paper_2604_19241_amd as moe
+
+    assert torch.cuda.is_available(), "bench.py needs an MI355X"
+    torch.cuda.set_device(0)
+    cfg = moe_synth.CONFIGS[args.config]
+    shape = moe.make_shape(**cfg.shape_dict())
+    sizes = moe.moe_workspace_bytes(shape)
+    has_bwd = cfg.backward and not args.no_backward and sizes["bwd"] > 256
+
+    inp = moe_synth.make_inputs(cfg, with_dy=has_bwd)
+    dev = {k: v.cuda() for k, v in inp.items()}
+    opts = moe.make_opts(schedule=args.schedule, tile_rows=args.tile_rows, workers=args.workers)
+    ws_route = torch.empty(sizes["route"], dtype=torch.uint8, device="cuda")
+    ws_fwd = torch.empty(sizes["fwd"], dtype=torch.uint8, device="cuda")
+    ws_bwd = torch.empty(sizes["bwd"], dtype=torch.uint8, device="cuda") if has_bwd else None
+    saved = moe.alloc_saved(shape, "cuda") if has_bwd else None
+    y = torch.empty((cfg.T, cfg.d), dtype=torch.bfloat16, device="cuda")
+    state = {}
+
+    def route():
+        state["r"] = moe.moe_route(shape, dev["logits"], ws=ws_route)
+
+    def fwd():
+        moe.moe_fused_forward(shape, dev["x"], dev["w_gate"], dev["w_up"], dev["w_down"],
+                              state["r"], y=y, saved=saved, ws=ws_fwd, opts=opts)
+
+    grads = {}
+
+    def bwd():
+        out = moe.moe_fused_backward(shape, dev["dy"], dev["x"], dev["w_gate"], dev["w_up"],
+                                     dev["w_down"], state["r"], saved, ws=ws_bwd, opts=opts,
+                                     out=grads.get("out"))
+        grads["out"] = out
+
+    def step():
+        route()
+        fwd()
+        if has_bwd:
+            bwd()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    assert moe.moe_device_status(ws_fwd) == 0
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+
+    A = int(state["r"].offsets[-1].item())
+    f_fwd = 6.0 * A * cfg.d * cfg.I
+    f_bwd = 12.0 * A * cfg.d * cfg.I if has_bwd else 0.0
+    value = (f_fwd + f_bwd) / (ms_per_step * 1e-3) / 1e12
+
+    # per-call timings with HIP events on the launch stream
+    n = max(10, min(args.steps, 100))
+    ms_route = event_ms(route, n)
+    ms_fwd = event_ms(fwd, n)
+    ms_bwd = event_ms(bwd, n) if has_bwd else None
+    fwd_tflops = f_fwd / (ms_fwd[0] * 1e-3) / 1e12
+    roofline = {
+        "kernel": "fwd_worker_kernel (forward MegaKernel, incl. its 1-block prologue launch)",
+        "bound": "mfma",
+        "achieved": fwd_tflops,
+        "peak": MFMA_BF16_PEAK_TFLOPS,
+        "unit": "TFLOP/s",
+        "frac": fwd_tflops / MFMA_BF16_PEAK_TFLOPS,
+        "traffic": None,
+        "avg_ms": ms_fwd[0], "median_ms": ms_fwd[1], "min_ms": ms_fwd[2],
+    }
+    counts = state["r"].counts.cpu().tolist()
+    out = {
+        "metric": "fused MoE fwd+bwd TFLOP/s" if has_bwd else "fused MoE fwd TFLOP/s",
+        "value": value,
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": f"configs[{args.config}] {cfg.name}: T={cfg.T} d={cfg.d} E={cfg.E} "
+                               f"k={cfg.k} I={cfg.I} local_experts={cfg.e_count}, route+forward"
+                               f"{'+backward' if has_bwd else ''}",
+                   "routed_rows": A, "schedule": args.schedule, "tile_rows": args.tile_rows},
+        "tokens_per_s": cfg.T / (ms_per_step * 1e-3),
+        "pct_of_bf16_mfma_peak": 100.0 * value / MFMA_BF16_PEAK_TFLOPS,
+        "phases_ms": {"route": ms_route[0], "forward": ms_fwd[0],
+                      "backward": ms_bwd[0] if ms_bwd else None},
+        "forward_tflops": fwd_tflops,
+        "backward_tflops": (f_bwd / (ms_bwd[0] * 1e-3) / 1e12) if ms_bwd else None,
+        "expert_load": moe_synth.histogram_summary(counts),
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, inp, has_bwd, args.cpu_seconds)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

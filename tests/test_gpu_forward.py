@@ -48,7 +48,8 @@ def check_forward(cfg, seed, schedule, tile_rows, wscale=1.0):
         yg = to_f64(y)
         e_abs, e_rel = max_abs(yg, want["y"]), rel_l2(yg, want["y"])
         say(f"   vs oracle[{acc}]: y max_abs={e_abs:.3e} rel_l2={e_rel:.3e}")
-        assert e_abs <= MAX_ABS and e_rel <= REL_L2
+        # the absolute bound is stated for weights ~ N(0, 0.02^2); y scales with wscale^3
+        assert e_abs <= MAX_ABS * wscale ** 3 and e_rel <= REL_L2
         if A > 0:
             gu = to_f64(views["gu"][:A])
             assert rel_l2(gu[:, :cfg.I], want["G"]) <= REL_L2, "G"
