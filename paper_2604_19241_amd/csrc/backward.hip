@@ -1,10 +1,556 @@
-// placeholder until the backward kernels land
-#include "common.hpp"
+// Backward MegaKernel of the fused MoE layer.
+//
+// Paper: Section 2.1 "Backward Propagation and Numerical Stability": the
+// gradient of the output is dispatched to the experts with the same token
+// mapping, input gradients are grouped GEMMs over the row tiles, and the weight
+// gradients are "transposed" grouped GEMMs that reduce over an expert's rows.
+// Because the rows of an expert sit in the deterministic order of Algorithm 1
+// and every tile walks them front to back in one workgroup, the accumulation
+// order of every dW element is fixed: bitwise reproducible, no float atomics,
+// no split of the reduction.  Scheduling follows Section 3.1 (one work queue,
+// scoreboard, producers before consumers).
+//
+// Phases (task ids ascending; a task only ever waits on lower ids):
+//   0  dH = dO W_down^T per row tile, dO = gate*dY gathered on the fly;
+//      SwiGLU backward in the epilogue -> dG|dU                       (MFMA)
+//   1  dW_down[e] = h_e^T dO_e            (no dependency: fills the queue)
+//   2  dXp = dG W_gate^T + dU W_up^T per row tile (one GEMM over k = 2I)
+//   3  dW_gate[e], dW_up[e] = x_e^T dG_e, x_e^T dU_e
+//   4  dX[t] = sum_j dXp[row(t,j)] in slot order; dtopk_w = <dY[t], o[row]>
+#include "tiles.hpp"
+
 namespace uniep {
-size_t bwd_workspace_bytes(const moe_shape_t& s) { (void)s; return 256; }
-int bwd_launch(const moe_shape_t&, const void*, const void*, const void*, const void*, const void*,
-               const moe_routing_t&, const char*, const char*, const char*, void*, void*, void*,
-               void*, float*, char*, const moe_opts_t&, int, hipStream_t) {
-    return MOE_ERR_HIP;
+
+enum BwdTask { B_DH = 0, B_DWD = 1, B_DXP = 2, B_DWGU = 3, B_DX = 4 };
+constexpr int kDxTokens = 16;
+
+struct BwdParams {
+    moe_shape_t s;
+    const char* dy;
+    const char* x;
+    const char* w_gate;
+    const char* w_up;
+    const char* w_down;
+    const float* topk_w;
+    const int32_t* offsets;
+    const int32_t* perm;
+    const int32_t* inv_perm;
+    const char* gu;   // saved G|U [A,2I]
+    const char* h;    // saved h [A,I]
+    const char* o;    // saved o [A,d]
+    char* dx;
+    char* dw_gate;
+    char* dw_up;
+    char* dw_down;
+    float* dtopk_w;
+    int* ctrl;
+    RowTile* rt;
+    int* flag_rt;   // per row tile: dH column tiles finished
+    int* flag_e;    // per expert: dH tiles finished
+    int* need_e;    // per expert: dH tiles it has
+    Task* tasks;
+    int32_t* row_tok;
+    float* row_w;
+    char* dgu;   // [A,2I]
+    char* dxp;   // [A,d]
+    int nct_dh, nct_dxp;        // column tiles of phase 0 (256 of I) and phase 2 (256 of d)
+    int mt_dwd, nt_dwd;         // dW_down tiles per expert: ceil(I/256) x ceil(d/256)
+    int mt_dwgu, nt_dwgu;       // dW_gate/up tiles per expert: ceil(d/256) x ceil(I/128)
+    long long spin_ticks;
+};
+
+// ------------------------------------------------------------- row metadata
+// row_tok[r] = token of expert row r, row_w[r] = its gate (the backward
+// "dispatch" of dY is a gather through these).
+__global__ void __launch_bounds__(256) row_meta_kernel(BwdParams p) {
+    const int A = p.offsets[p.s.e_count];
+    const int r = blockIdx.x * 256 + threadIdx.x;
+    if (r < A) {
+        const int f = p.perm[r];
+        p.row_tok[r] = f / p.s.k;
+        p.row_w[r] = p.topk_w[f];
+    }
 }
+
+template <int BM>
+__global__ void __launch_bounds__(1024) bwd_prologue_kernel(BwdParams p) {
+    __shared__ int32_t s_scan[kMaxExperts];
+    const int e = threadIdx.x;
+    const int ec = p.s.e_count;
+    int cnt = 0, nt = 0;
+    if (e < ec) {
+        cnt = p.offsets[e + 1] - p.offsets[e];
+        nt = (cnt + BM - 1) / BM;
+    }
+    s_scan[e] = nt;
+    __syncthreads();
+    for (int off = 1; off < kMaxExperts; off <<= 1) {
+        const int32_t add = (e >= off) ? s_scan[e - off] : 0;
+        __syncthreads();
+        s_scan[e] += add;
+        __syncthreads();
+    }
+    const int nrt = s_scan[kMaxExperts - 1];
+    if (e < ec) {
+        const int base = s_scan[e] - nt;
+        const int r0 = p.offsets[e];
+        for (int i = 0; i < nt; ++i) {
+            RowTile t;
+            t.expert = e;
+            t.row0 = r0 + i * BM;
+            t.rows = min(BM, cnt - i * BM);
+            t.pad = 0;
+            p.rt[base + i] = t;
+        }
+        p.flag_e[e] = 0;
+        p.need_e[e] = nt * p.nct_dh;
+    }
+    const int n0 = nrt * p.nct_dh;
+    const int per1 = p.mt_dwd * p.nt_dwd, n1 = ec * per1;
+    const int n2 = nrt * p.nct_dxp;
+    const int per3 = p.mt_dwgu * p.nt_dwgu, n3 = ec * per3;
+    const int n4 = (p.s.T + kDxTokens - 1) / kDxTokens;
+    Task* t = p.tasks;
+    for (int i = e; i < n0; i += 1024) t[i] = Task{i / p.nct_dh, (B_DH << 20) | (i % p.nct_dh)};
+    t += n0;
+    for (int i = e; i < n1; i += 1024) {
+        const int ex = i / per1, r = i % per1;
+        t[i] = Task{ex * p.mt_dwd + r / p.nt_dwd, (B_DWD << 20) | (r % p.nt_dwd)};
+    }
+    t += n1;
+    for (int i = e; i < n2; i += 1024) t[i] = Task{i / p.nct_dxp, (B_DXP << 20) | (i % p.nct_dxp)};
+    t += n2;
+    for (int i = e; i < n3; i += 1024) {
+        const int ex = i / per3, r = i % per3;
+        t[i] = Task{ex * p.mt_dwgu + r / p.nt_dwgu, (B_DWGU << 20) | (r % p.nt_dwgu)};
+    }
+    t += n3;
+    for (int i = e; i < n4; i += 1024) t[i] = Task{i, (B_DX << 20)};
+    for (int i = e; i < nrt; i += 1024) p.flag_rt[i] = 0;
+    if (e < CTRL_WORDS) {
+        const int ends[5] = {n0, n0 + n1, n0 + n1 + n2, n0 + n1 + n2 + n3, n0 + n1 + n2 + n3 + n4};
+        int v = 0;
+        if (e == CTRL_NRT) v = nrt;
+        if (e == CTRL_NTASK) v = ends[4];
+        for (int ph = 0; ph < 5; ++ph) {
+            if (e == CTRL_PHASE_END + ph) v = ends[ph];
+            if (ph > 0 && e == CTRL_CURSOR + 1 + ph) v = ends[ph - 1];
+        }
+        p.ctrl[e] = v;
+    }
+}
+
+// ------------------------------------------------------------- phase 0: dH
+template <int FM>
+__device__ __forceinline__ void dh_task(const BwdParams& p, const RowTile rt, int ct, char* smem) {
+    const int d = p.s.d, I = p.s.I;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int mrow = tid >> 3, kc = tid & 7;
+    RowLoader<4 * FM, true> al;
+    al.init();
+#pragma unroll
+    for (int q = 0; q < 4 * FM; ++q) {
+        const int row = rt.row0 + min(mrow + 32 * q, rt.rows - 1);
+        al.rp[q] = p.dy + ((size_t)p.row_tok[row] * d + kc * 8) * 2;
+        al.sc[q] = p.row_w[row];
+    }
+    RowLoader<8, false> bl;   // B rows are rows of W_down[e]: k (= d) contiguous
+    bl.init();
+    const int n0 = ct * BN;
+    {
+        const int c0 = min(n0 + mrow * 8, I - 8);
+#pragma unroll
+        for (int q = 0; q < 8; ++q)
+            bl.rp[q] = p.w_down + (((size_t)rt.expert * I + c0 + q) * d + kc * 8) * 2;
+    }
+    f32x16_t acc[FM][8];
+    mma_mainloop<FM>(al, bl, d / BK, smem, acc);
+    // epilogue: SwiGLU backward with the saved G, U of the same rows and columns
+    const int col = n0 + (lane & 31) * 8;
+    if (col < I) {
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int m = (wave * FM + i) * 32 + frag_row(v, lane);
+                if (m < rt.rows) {
+                    const size_t base = ((size_t)(rt.row0 + m) * 2 * I + col) * 2;
+                    const u32x4_t gv = *(const u32x4_t*)(p.gu + base);
+                    const u32x4_t uv = *(const u32x4_t*)(p.gu + base + (size_t)I * 2);
+                    float dg[8], du[8];
+#pragma unroll
+                    for (int f = 0; f < 8; ++f) {
+                        const float g = (f & 1) ? bf16_hi(gv[f >> 1]) : bf16_lo(gv[f >> 1]);
+                        const float u = (f & 1) ? bf16_hi(uv[f >> 1]) : bf16_lo(uv[f >> 1]);
+                        const float dh = acc[i][f][v];
+                        const float sg = sigmoid_f(g);
+                        du[f] = dh * (g * sg);
+                        dg[f] = dh * u * (sg * (1.f + g * (1.f - sg)));
+                    }
+                    u32x4_t dgp, dup;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        dgp[q] = pack_bf16x2(dg[2 * q], dg[2 * q + 1]);
+                        dup[q] = pack_bf16x2(du[2 * q], du[2 * q + 1]);
+                    }
+                    *(u32x4_t*)(p.dgu + base) = dgp;
+                    *(u32x4_t*)(p.dgu + base + (size_t)I * 2) = dup;
+                }
+            }
+    }
+}
+
+// ------------------------------------------------------------- phase 2: dXp
+template <int FM>
+__device__ __forceinline__ void dxp_task(const BwdParams& p, const RowTile rt, int ct, char* smem) {
+    const int d = p.s.d, I = p.s.I;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int mrow = tid >> 3, kc = tid & 7;
+    RowLoader<4 * FM, false> al;
+    al.init();
+#pragma unroll
+    for (int q = 0; q < 4 * FM; ++q) {
+        const int row = rt.row0 + min(mrow + 32 * q, rt.rows - 1);
+        al.rp[q] = p.dgu + ((size_t)row * 2 * I + kc * 8) * 2;
+    }
+    SplitRowLoader<8> bl;   // k < I: row of W_gate[e][dcol], k >= I: row of W_up[e][dcol]
+    bl.init();
+    const int n0 = ct * BN;
+    {
+        const int c0 = min(n0 + mrow * 8, d - 8);
+#pragma unroll
+        for (int q = 0; q < 8; ++q)
+            bl.rp[q] = p.w_gate + (((size_t)rt.expert * d + c0 + q) * I + kc * 8) * 2;
+        bl.delta = (long long)(p.w_up - p.w_gate);
+        bl.switch_stage = I / BK;
+    }
+    f32x16_t acc[FM][8];
+    mma_mainloop<FM>(al, bl, 2 * I / BK, smem, acc);
+    const int col = n0 + (lane & 31) * 8;
+    if (col < d) {
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int m = (wave * FM + i) * 32 + frag_row(v, lane);
+                if (m < rt.rows)
+                    *(u32x4_t*)(p.dxp + ((size_t)(rt.row0 + m) * d + col) * 2) = pack_row8<FM>(acc, i, v);
+            }
+    }
+}
+
+// Output row (within the 256-row tile) of accumulator (fragment i, element v)
+// when the A operand went through a transposing loader: LDS row j*32+mb holds
+// m = mb*8 + j, wave w reads rows [64w, 64w+64), so j = 2w+i and mb = frag row.
+__device__ __forceinline__ int tr_out_row(int wave, int i, int v, int lane) {
+    return frag_row(v, lane) * 8 + 2 * wave + i;
+}
+
+// ------------------------------------------------------------- phase 1: dW_down
+// dW_down[e][i][c] = sum over the expert's rows r (ascending) of h[r][i] * dO[r][c].
+__device__ __forceinline__ void dwd_task(const BwdParams& p, int e, int mt, int nt, char* smem) {
+    const int d = p.s.d, I = p.s.I;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int r0 = p.offsets[e], cnt = p.offsets[e + 1] - r0;
+    const int cb = tid & 31;
+    StridedLoaderK al;
+    al.init();
+    al.ld_bytes = (size_t)I * 2;
+    al.K = cnt;
+    al.bp = p.h + ((size_t)r0 * I + min(mt * 256 + cb * 8, I - 8)) * 2;
+    GatherStridedLoader<true> bl;
+    bl.init();
+    bl.ld_bytes = (size_t)d * 2;
+    bl.row_tok = p.row_tok;
+    bl.row_w = p.row_w;
+    bl.row0 = r0;
+    bl.K = cnt;
+    bl.src = p.dy + (size_t)min(nt * 256 + cb * 8, d - 8) * 2;
+    f32x16_t acc[2][8];
+    mma_mainloop<2>(al, bl, (cnt + BK - 1) / BK, smem, acc);
+    const int col = nt * 256 + (lane & 31) * 8;
+    if (col < d) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int m = mt * 256 + tr_out_row(wave, i, v, lane);
+                if (m < I)
+                    *(u32x4_t*)(p.dw_down + (((size_t)e * I + m) * d + col) * 2) = pack_row8<2>(acc, i, v);
+            }
+    }
+}
+
+// ------------------------------------------------------------- phase 3: dW_gate, dW_up
+// dW_gate[e][c][i] = sum_r x[tok(r)][c] * dG[r][i]; dW_up likewise with dU.
+// B-tile chunk nb: even -> 8 columns of dG, odd -> the same 8 columns of dU.
+__device__ __forceinline__ void dwgu_task(const BwdParams& p, int e, int mt, int nt, char* smem) {
+    const int d = p.s.d, I = p.s.I;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int r0 = p.offsets[e], cnt = p.offsets[e + 1] - r0;
+    const int cb = tid & 31;
+    GatherStridedLoader<false> al;
+    al.init();
+    al.ld_bytes = (size_t)d * 2;
+    al.row_tok = p.row_tok;
+    al.row_w = p.row_w;
+    al.row0 = r0;
+    al.K = cnt;
+    al.src = p.x + (size_t)min(mt * 256 + cb * 8, d - 8) * 2;
+    StridedLoaderK bl;
+    bl.init();
+    bl.ld_bytes = (size_t)I * 4;
+    bl.K = cnt;
+    bl.bp = p.dgu + ((size_t)r0 * 2 * I + ((cb & 1) ? I : 0) + min(nt * 128 + (cb >> 1) * 8, I - 8)) * 2;
+    f32x16_t acc[2][8];
+    mma_mainloop<2>(al, bl, (cnt + BK - 1) / BK, smem, acc);
+    const int nb = lane & 31;
+    const int icol = nt * 128 + (nb >> 1) * 8;
+    char* dst = (nb & 1) ? p.dw_up : p.dw_gate;
+    if (icol < I) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int m = mt * 256 + tr_out_row(wave, i, v, lane);
+                if (m < d)
+                    *(u32x4_t*)(dst + (((size_t)e * d + m) * I + icol) * 2) = pack_row8<2>(acc, i, v);
+            }
+    }
+}
+
+// ------------------------------------------------------------- phase 4: dX, dtopk_w
+__device__ __forceinline__ void dx_task(const BwdParams& p, int block) {
+    const int d = p.s.d, k = p.s.k, T = p.s.T;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int tt = wave; tt < kDxTokens; tt += 4) {
+        const int t = block * kDxTokens + tt;
+        if (t >= T) break;
+        int rows[kMaxTopK];
+#pragma unroll
+        for (int j = 0; j < kMaxTopK; ++j) rows[j] = (j < k) ? p.inv_perm[(size_t)t * k + j] : -1;
+        float dots[kMaxTopK];
+#pragma unroll
+        for (int j = 0; j < kMaxTopK; ++j) dots[j] = 0.f;
+        for (int c = lane * 8; c < d; c += 64 * 8) {
+            float a[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) a[q] = 0.f;
+            u32x4_t dyv = zero4();
+            if (p.dtopk_w) dyv = *(const u32x4_t*)(p.dy + ((size_t)t * d + c) * 2);
+#pragma unroll
+            for (int j = 0; j < kMaxTopK; ++j) {
+                if (j < k && rows[j] >= 0) {
+                    const u32x4_t v = *(const u32x4_t*)(p.dxp + ((size_t)rows[j] * d + c) * 2);
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        a[2 * q] += bf16_lo(v[q]);
+                        a[2 * q + 1] += bf16_hi(v[q]);
+                    }
+                    if (p.dtopk_w) {
+                        const u32x4_t ov = *(const u32x4_t*)(p.o + ((size_t)rows[j] * d + c) * 2);
+#pragma unroll
+                        for (int q = 0; q < 4; ++q)
+                            dots[j] += bf16_lo(dyv[q]) * bf16_lo(ov[q]) + bf16_hi(dyv[q]) * bf16_hi(ov[q]);
+                    }
+                }
+            }
+            u32x4_t out;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) out[q] = pack_bf16x2(a[2 * q], a[2 * q + 1]);
+            *(u32x4_t*)(p.dx + ((size_t)t * d + c) * 2) = out;
+        }
+        if (p.dtopk_w) {
+#pragma unroll
+            for (int j = 0; j < kMaxTopK; ++j) {
+                if (j < k) {
+                    float s = dots[j];
+#pragma unroll
+                    for (int off = 32; off >= 1; off >>= 1) s += __shfl_xor(s, off);
+                    if (lane == 0) p.dtopk_w[(size_t)t * k + j] = (rows[j] >= 0) ? s : 0.f;
+                }
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------- worker loop
+template <int FM>
+__global__ void __launch_bounds__(kTileThreads) __attribute__((amdgpu_waves_per_eu(1, 1)))
+bwd_worker_kernel(BwdParams p, int phase) {
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    __shared__ int s_task;
+    __shared__ int s_ok;
+    int* ctrl = p.ctrl;
+    const int end = (phase < 0) ? ctrl[CTRL_NTASK] : ctrl[CTRL_PHASE_END + phase];
+    int* cursor = ctrl + CTRL_CURSOR + (phase < 0 ? 0 : 1 + phase);
+    const int n_dxp = ctrl[CTRL_PHASE_END + 2] - ctrl[CTRL_PHASE_END + 1];
+    for (;;) {
+        if (threadIdx.x == 0) s_task = atomicAdd(cursor, 1);
+        __syncthreads();
+        const int id = s_task;
+        if (id >= end) break;
+        const Task task = p.tasks[id];
+        const int type = task.type_ct >> 20, ct = task.type_ct & 0xfffff;
+        if (type == B_DH) {
+            const RowTile rt = p.rt[task.rt];
+            dh_task<FM>(p, rt, ct, smem);
+            __syncthreads();
+            if (threadIdx.x == 0) {
+                add_release(p.flag_rt + task.rt, 1);
+                add_release(p.flag_e + rt.expert, 1);
+            }
+        } else if (type == B_DWD) {
+            dwd_task(p, task.rt / p.mt_dwd, task.rt % p.mt_dwd, ct, smem);
+        } else if (type == B_DXP) {
+            if (threadIdx.x == 0) s_ok = wait_ge(p.flag_rt + task.rt, p.nct_dh, ctrl, p.spin_ticks);
+            __syncthreads();
+            if (s_ok) {
+                const RowTile rt = p.rt[task.rt];
+                dxp_task<FM>(p, rt, ct, smem);
+            }
+            __syncthreads();
+            if (threadIdx.x == 0) add_release(ctrl + CTRL_DONE + 2, 1);
+        } else if (type == B_DWGU) {
+            const int e = task.rt / p.mt_dwgu;
+            if (threadIdx.x == 0) s_ok = wait_ge(p.flag_e + e, p.need_e[e], ctrl, p.spin_ticks);
+            __syncthreads();
+            if (s_ok) dwgu_task(p, e, task.rt % p.mt_dwgu, ct, smem);
+        } else {
+            if (threadIdx.x == 0) s_ok = wait_ge(ctrl + CTRL_DONE + 2, n_dxp, ctrl, p.spin_ticks);
+            __syncthreads();
+            if (s_ok) dx_task(p, task.rt);
+        }
+        __syncthreads();
+    }
+}
+
+// ------------------------------------------------------------------ host side
+
+struct BwdLayout {
+    size_t ctrl, rt, flag_rt, flag_e, need_e, tasks, row_tok, row_w, dgu, dxp, total;
+    int max_rt, nct_dh, nct_dxp, mt_dwd, nt_dwd, mt_dwgu, nt_dwgu;
+};
+
+static BwdLayout bwd_layout(const moe_shape_t& s) {
+    BwdLayout L;
+    const size_t A_cap = (size_t)s.T * s.k;
+    L.max_rt = (int)((A_cap + 127) / 128) + s.e_count;
+    L.nct_dh = (s.I + BN - 1) / BN;
+    L.nct_dxp = (s.d + BN - 1) / BN;
+    L.mt_dwd = (s.I + 255) / 256;
+    L.nt_dwd = (s.d + 255) / 256;
+    L.mt_dwgu = (s.d + 255) / 256;
+    L.nt_dwgu = (s.I + 127) / 128;
+    const size_t max_tasks = (size_t)L.max_rt * (L.nct_dh + L.nct_dxp) +
+                             (size_t)s.e_count * (L.mt_dwd * L.nt_dwd + L.mt_dwgu * L.nt_dwgu) +
+                             (s.T + kDxTokens - 1) / kDxTokens;
+    size_t off = 0;
+    L.ctrl = off;    off = align_up(off + CTRL_WORDS * sizeof(int), 256);
+    L.rt = off;      off = align_up(off + (size_t)L.max_rt * sizeof(RowTile), 256);
+    L.flag_rt = off; off = align_up(off + (size_t)L.max_rt * sizeof(int), 256);
+    L.flag_e = off;  off = align_up(off + (size_t)s.e_count * sizeof(int), 256);
+    L.need_e = off;  off = align_up(off + (size_t)s.e_count * sizeof(int), 256);
+    L.tasks = off;   off = align_up(off + max_tasks * sizeof(Task), 256);
+    L.row_tok = off; off = align_up(off + A_cap * sizeof(int32_t), 256);
+    L.row_w = off;   off = align_up(off + A_cap * sizeof(float), 256);
+    L.dgu = off;     off = align_up(off + A_cap * 2 * s.I * 2, 256);
+    L.dxp = off;     off = align_up(off + A_cap * s.d * 2, 256);
+    L.total = off;
+    return L;
+}
+
+size_t bwd_workspace_bytes(const moe_shape_t& s) { return bwd_layout(s).total; }
+
+static int g_bwd_workers[16];
+
+template <int FM>
+static int bwd_resident_workers(int* out) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return MOE_ERR_HIP;
+    const int slot = (dev & 7) * 2 + (FM - 1);
+    if (g_bwd_workers[slot] == 0) {
+        if (hipFuncSetAttribute((const void*)bwd_worker_kernel<FM>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize,
+                                Geom<2>::SMEM) != hipSuccess)
+            return MOE_ERR_HIP;
+        int per_cu = 0, cus = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, bwd_worker_kernel<FM>, kTileThreads,
+                                                         Geom<2>::SMEM) != hipSuccess)
+            return MOE_ERR_HIP;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+            return MOE_ERR_HIP;
+        if (per_cu < 1 || cus < 1) return MOE_ERR_HIP;
+        g_bwd_workers[slot] = per_cu * cus;
+    }
+    *out = g_bwd_workers[slot];
+    return MOE_OK;
+}
+
+template <int FM>
+static int bwd_launch_fm(BwdParams& p, const moe_opts_t& opts, hipStream_t st) {
+    int resident = 0;
+    int rc = bwd_resident_workers<FM>(&resident);
+    if (rc != MOE_OK) return rc;
+    const int workers = opts.workers > 0 ? min(opts.workers, resident) : resident;
+    const int A_cap = p.s.T * p.s.k;
+    if (A_cap > 0)
+        hipLaunchKernelGGL(row_meta_kernel, dim3((A_cap + 255) / 256), dim3(256), 0, st, p);
+    hipLaunchKernelGGL(bwd_prologue_kernel<Geom<FM>::BM>, dim3(1), dim3(1024), 0, st, p);
+    if (opts.schedule == 2) {
+        for (int phase = 0; phase < 5; ++phase)
+            hipLaunchKernelGGL(bwd_worker_kernel<FM>, dim3(workers), dim3(kTileThreads),
+                               Geom<2>::SMEM, st, p, phase);
+    } else {
+        hipLaunchKernelGGL(bwd_worker_kernel<FM>, dim3(workers), dim3(kTileThreads), Geom<2>::SMEM,
+                           st, p, -1);
+    }
+    return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
+}
+
+int bwd_launch(const moe_shape_t& s, const void* dy, const void* x, const void* w_gate,
+               const void* w_up, const void* w_down, const moe_routing_t& r, const char* gu,
+               const char* h, const char* o, void* dx, void* dw_gate, void* dw_up, void* dw_down,
+               float* dtopk_w, char* ws, const moe_opts_t& opts, int fm, hipStream_t st) {
+    const BwdLayout L = bwd_layout(s);
+    BwdParams p;
+    p.s = s;
+    p.dy = (const char*)dy;
+    p.x = (const char*)x;
+    p.w_gate = (const char*)w_gate;
+    p.w_up = (const char*)w_up;
+    p.w_down = (const char*)w_down;
+    p.topk_w = r.topk_w;
+    p.offsets = r.offsets;
+    p.perm = r.perm;
+    p.inv_perm = r.inv_perm;
+    p.gu = gu;
+    p.h = h;
+    p.o = o;
+    p.dx = (char*)dx;
+    p.dw_gate = (char*)dw_gate;
+    p.dw_up = (char*)dw_up;
+    p.dw_down = (char*)dw_down;
+    p.dtopk_w = dtopk_w;
+    p.ctrl = (int*)(ws + L.ctrl);
+    p.rt = (RowTile*)(ws + L.rt);
+    p.flag_rt = (int*)(ws + L.flag_rt);
+    p.flag_e = (int*)(ws + L.flag_e);
+    p.need_e = (int*)(ws + L.need_e);
+    p.tasks = (Task*)(ws + L.tasks);
+    p.row_tok = (int32_t*)(ws + L.row_tok);
+    p.row_w = (float*)(ws + L.row_w);
+    p.dgu = ws + L.dgu;
+    p.dxp = ws + L.dxp;
+    p.nct_dh = L.nct_dh;
+    p.nct_dxp = L.nct_dxp;
+    p.mt_dwd = L.mt_dwd;
+    p.nt_dwd = L.nt_dwd;
+    p.mt_dwgu = L.mt_dwgu;
+    p.nt_dwgu = L.nt_dwgu;
+    const int ms = opts.spin_limit_ms > 0 ? opts.spin_limit_ms : 2000;
+    p.spin_ticks = (long long)ms * 100000ll;
+    return fm == 1 ? bwd_launch_fm<1>(p, opts, st) : bwd_launch_fm<2>(p, opts, st);
+}
+
 }  // namespace uniep

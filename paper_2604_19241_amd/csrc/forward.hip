@@ -247,7 +247,8 @@ __device__ __forceinline__ void combine_task(const FwdParams& p, int block) {
 // phase >= 0: only that phase's tasks (staged schedule; the waits are already
 // satisfied by stream order).
 template <int FM>
-__global__ void __launch_bounds__(kTileThreads) fwd_worker_kernel(FwdParams p, int phase) {
+__global__ void __launch_bounds__(kTileThreads) __attribute__((amdgpu_waves_per_eu(1, 1)))
+fwd_worker_kernel(FwdParams p, int phase) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     __shared__ int s_task;
     __shared__ int s_ok;

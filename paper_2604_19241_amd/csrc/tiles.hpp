@@ -121,6 +121,107 @@ struct StridedLoader {
     }
 };
 
+// RowLoader whose k axis is the concatenation of two matrices with identical
+// layout (W_gate then W_up along k): stages >= switch_stage read from the
+// second matrix, which sits `delta` bytes after the first.
+template <int NROWS32>
+struct SplitRowLoader {
+    const char* rp[NROWS32];
+    u32x4_t reg[NROWS32];
+    long long delta;
+    int switch_stage;
+    int lds_off;
+
+    __device__ __forceinline__ void init() {
+        lds_off = (threadIdx.x >> 3) * kRowBytes + (threadIdx.x & 7) * 16;
+    }
+    __device__ __forceinline__ void gload(int s) {
+        const long long off = (s < switch_stage) ? (long long)s * (BK * 2)
+                                                 : delta + (long long)(s - switch_stage) * (BK * 2);
+#pragma unroll
+        for (int p = 0; p < NROWS32; ++p) reg[p] = *(const u32x4_t*)(rp[p] + off);
+    }
+    __device__ __forceinline__ void sstore(char* base) {
+#pragma unroll
+        for (int p = 0; p < NROWS32; ++p) *(u32x4_t*)(base + lds_off + p * 32 * kRowBytes) = reg[p];
+    }
+};
+
+// StridedLoader for a reduction over K memory rows where K is not a multiple
+// of 64 (the rows of one expert): rows at and beyond K are zero-filled.
+// bp = address of (k = 0, first column of chunk nb).
+struct StridedLoaderK {
+    const char* bp;
+    size_t ld_bytes;
+    int K;
+    u32x4_t reg[8];
+    int lds_off, kb8;
+
+    __device__ __forceinline__ void init() {
+        lds_off = (threadIdx.x & 31) * kRowBytes + (threadIdx.x >> 5) * 16;
+        kb8 = (threadIdx.x >> 5) * 8;
+    }
+    __device__ __forceinline__ void gload(int s) {
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            const int k = s * BK + kb8 + r;
+            const u32x4_t v = *(const u32x4_t*)(bp + (size_t)min(k, K - 1) * ld_bytes);
+            reg[r] = (k < K) ? v : zero4();
+        }
+    }
+    __device__ __forceinline__ void sstore(char* base) {
+        u32x4_t out[8];
+        transpose8x8(reg, out);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) *(u32x4_t*)(base + lds_off + j * 32 * kRowBytes) = out[j];
+    }
+};
+
+// The same with a gather: memory row of reduction index k is row_tok[row0+k]
+// of a [T, ld] matrix (the token that sits in that expert row), optionally
+// scaled by row_w[row0+k] and rounded to bf16 once (dO = gate * dY).
+// src = matrix base + byte offset of the first column of chunk nb.
+template <bool SCALE>
+struct GatherStridedLoader {
+    const char* src;
+    size_t ld_bytes;
+    const int32_t* row_tok;
+    const float* row_w;
+    int row0, K;
+    u32x4_t reg[8];
+    float sc[8];
+    int lds_off, kb8;
+
+    __device__ __forceinline__ void init() {
+        lds_off = (threadIdx.x & 31) * kRowBytes + (threadIdx.x >> 5) * 16;
+        kb8 = (threadIdx.x >> 5) * 8;
+    }
+    __device__ __forceinline__ void gload(int s) {
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            const int k = s * BK + kb8 + r;
+            const int row = row0 + min(k, K - 1);
+            const int tok = row_tok[row];
+            if (SCALE) sc[r] = row_w[row];
+            const u32x4_t v = *(const u32x4_t*)(src + (size_t)tok * ld_bytes);
+            reg[r] = (k < K) ? v : zero4();
+        }
+    }
+    __device__ __forceinline__ void sstore(char* base) {
+        if (SCALE) {
+#pragma unroll
+            for (int r = 0; r < 8; ++r)
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    reg[r][q] = pack_bf16x2(bf16_lo(reg[r][q]) * sc[r], bf16_hi(reg[r][q]) * sc[r]);
+        }
+        u32x4_t out[8];
+        transpose8x8(reg, out);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) *(u32x4_t*)(base + lds_off + j * 32 * kRowBytes) = out[j];
+    }
+};
+
 // ---------------------------------------------------------------- main loop
 // acc[i][f] += A-fragment i  x  B-fragment f over nk stages of 64.
 template <int FM, class AL, class BL>
@@ -134,6 +235,7 @@ __device__ __forceinline__ void mma_mainloop(AL& al, BL& bl, int nk, char* smem,
         for (int f = 0; f < 8; ++f)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][f][v] = 0.f;
+    if (nk <= 0) return;   // empty reduction (an expert without rows): the tile is all zeros
 
     al.gload(0);
     bl.gload(0);
@@ -159,6 +261,7 @@ __device__ __forceinline__ void mma_mainloop(AL& al, BL& bl, int nk, char* smem,
 #pragma unroll
         for (int kk = 0; kk < BK / 16; ++kk) {
             const int c = kk & 1, n = c ^ 1;
+            __builtin_amdgcn_sched_barrier(0);
             if (kk + 1 < BK / 16) {
 #pragma unroll
                 for (int i = 0; i < FM; ++i)
@@ -167,6 +270,7 @@ __device__ __forceinline__ void mma_mainloop(AL& al, BL& bl, int nk, char* smem,
                 for (int f = 0; f < 8; ++f)
                     b[n][f] = *(const bf16x8_t*)(cur + b_off + f * 32 * kRowBytes + (kk + 1) * 32);
             }
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int i = 0; i < FM; ++i)
 #pragma unroll

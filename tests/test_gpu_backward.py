@@ -1,0 +1,113 @@
+"""GPU parity of moe_fused_backward against the oracle: dX, dW_gate, dW_up,
+dW_down, dtopk_w element by element on sizes with several tiles and ragged
+tails, both schedules and tile heights; exact zeros for idle experts; bitwise
+repeatability (the paper's max_diff = 0 criterion applied run to run)."""
+import numpy as np
+import pytest
+import torch
+
+import moe_synth
+import oracle
+from helpers import bits, rel_l2, say, scaled_inputs, to_f64
+
+pytestmark = pytest.mark.gpu
+
+GRAD_REL_L2 = 1e-2   # the benchmark spec tolerance for gradients
+KEYS = ("dx", "dw_gate", "dw_up", "dw_down")
+
+
+def gpu_fwd_bwd(cfg, inp, schedule, tile_rows, workers=0, want_dtopk_w=True):
+    import paper_2604_19241_amd as moe
+    shape = moe.make_shape(**cfg.shape_dict())
+    dev = {key: v.cuda() for key, v in inp.items()}
+    routing = moe.moe_route(shape, dev["logits"])
+    saved = moe.alloc_saved(shape, "cuda")
+    sizes = moe.moe_workspace_bytes(shape)
+    ws = torch.empty(sizes["fwd"], dtype=torch.uint8, device="cuda")
+    wsb = torch.empty(sizes["bwd"], dtype=torch.uint8, device="cuda")
+    opts = moe.make_opts(schedule=schedule, tile_rows=tile_rows, workers=workers,
+                         spin_limit_ms=500)
+    moe.moe_fused_forward(shape, dev["x"], dev["w_gate"], dev["w_up"], dev["w_down"], routing,
+                          saved=saved, ws=ws, opts=opts)
+    g = moe.moe_fused_backward(shape, dev["dy"], dev["x"], dev["w_gate"], dev["w_up"],
+                               dev["w_down"], routing, saved, want_dtopk_w=want_dtopk_w, ws=wsb,
+                               opts=opts)
+    assert moe.moe_device_status(ws) == 0
+    assert moe.moe_device_status(wsb) == 0
+    return g, routing
+
+
+def check_backward(cfg, seed, schedule, tile_rows, wscale):
+    say(f"[bwd] {cfg.shape_dict()} schedule={schedule} tile_rows={tile_rows} wscale={wscale}")
+    inp = scaled_inputs(cfg, seed, wscale)
+    b = bits(inp, ("x", "dy", "w_gate", "w_up", "w_down"))
+    r = oracle.route(cfg.shape_dict(), inp["logits"].numpy())
+    g, _ = gpu_fwd_bwd(cfg, inp, schedule, tile_rows)
+    for acc in ("f64", "f32"):
+        want = oracle.backward(cfg.shape_dict(), b["x"], b["dy"], b["w_gate"], b["w_up"],
+                               b["w_down"], r, round_bf16=True, acc=acc)
+        errs = {key: rel_l2(to_f64(g[key]), want[key]) for key in KEYS}
+        errs["dtopk_w"] = rel_l2(to_f64(g["dtopk_w"]), want["dtopk_w"])
+        say(f"   vs oracle[{acc}]: " + " ".join(f"{k}={v:.2e}" for k, v in errs.items()))
+        for key, v in errs.items():
+            assert v <= GRAD_REL_L2, (key, v)
+        # idle experts: exact zeros
+        for e in np.nonzero(r["counts"] == 0)[0]:
+            for key in ("dw_gate", "dw_up", "dw_down"):
+                assert (g[key][int(e)] == 0).all(), (key, e)
+    return g
+
+
+SMALL = [
+    dict(T=700, d=320, E=4, k=2, I=320),
+    dict(T=256, d=512, E=8, k=2, I=1024),
+    dict(T=300, d=256, E=16, k=4, I=192, e_start=4, e_count=8),
+    dict(T=97, d=128, E=32, k=8, I=64),
+]
+
+
+@pytest.mark.parametrize("kw", SMALL)
+@pytest.mark.parametrize("schedule", [2, 1])
+@pytest.mark.parametrize("tile_rows", [128, 256])
+def test_backward_matches_oracle(kw, schedule, tile_rows):
+    cfg = moe_synth.small_config(**kw)
+    check_backward(cfg, seed=13, schedule=schedule, tile_rows=tile_rows, wscale=4.0)
+
+
+def test_backward_config0_default_options():
+    check_backward(moe_synth.CONFIGS[0], seed=None, schedule=0, tile_rows=0, wscale=1.0)
+
+
+def test_backward_idle_experts_and_skew():
+    cfg = moe_synth.small_config(T=500, d=128, E=16, k=2, I=128, zipf_s=3.0)
+    inp = scaled_inputs(cfg, 5, 4.0)
+    r = oracle.route(cfg.shape_dict(), inp["logits"].numpy())
+    assert (r["counts"] == 0).any() and r["counts"].max() > 300
+    check_backward(cfg, seed=5, schedule=1, tile_rows=0, wscale=4.0)
+
+
+def test_backward_is_bitwise_repeatable_and_schedule_independent():
+    cfg = moe_synth.small_config(T=900, d=256, E=16, k=4, I=256, zipf_s=1.2)
+    inp = scaled_inputs(cfg, 22, 4.0)
+    say("[bwd] determinism 10 runs, persistent")
+    ref, _ = gpu_fwd_bwd(cfg, inp, 1, 0)
+    ref = {k: v.clone() for k, v in ref.items()}
+    for i in range(9):
+        again, _ = gpu_fwd_bwd(cfg, inp, 1, 0)
+        for key in ref:
+            assert torch.equal(ref[key], again[key]), (key, i + 1)
+    say("[bwd] determinism across schedules, worker counts and tile heights")
+    for schedule, workers, tile_rows in ((2, 0, 0), (1, 5, 0), (1, 64, 0), (1, 0, 128), (1, 0, 256)):
+        other, _ = gpu_fwd_bwd(cfg, inp, schedule, tile_rows, workers=workers)
+        for key in ref:
+            assert torch.equal(ref[key], other[key]), (key, schedule, workers, tile_rows)
+
+
+def test_backward_without_dtopk_w():
+    cfg = moe_synth.small_config(T=200, d=128, E=8, k=2, I=128)
+    inp = scaled_inputs(cfg, 9, 4.0)
+    g1, _ = gpu_fwd_bwd(cfg, inp, 1, 0, want_dtopk_w=True)
+    g2, _ = gpu_fwd_bwd(cfg, inp, 1, 0, want_dtopk_w=False)
+    assert g2["dtopk_w"] is None
+    for key in KEYS:
+        assert torch.equal(g1[key], g2[key])
