@@ -10,12 +10,12 @@ size_t fwd_workspace_bytes(const moe_shape_t& s);
 size_t fwd_ctrl_bytes(const moe_shape_t& s);
 int fwd_launch(const moe_shape_t& s, const void* x, const void* w_gate, const void* w_up,
                const void* w_down, const moe_routing_t& r, void* y, char* gu, char* h, char* o,
-               char* ws, const moe_opts_t& opts, int fm, hipStream_t st);
+               char* ws, const moe_opts_t& opts, int nw, hipStream_t st);
 size_t bwd_workspace_bytes(const moe_shape_t& s);
 int bwd_launch(const moe_shape_t& s, const void* dy, const void* x, const void* w_gate,
                const void* w_up, const void* w_down, const moe_routing_t& r, const char* gu,
                const char* h, const char* o, void* dx, void* dw_gate, void* dw_up, void* dw_down,
-               float* dtopk_w, char* ws, const moe_opts_t& opts, int fm, hipStream_t st);
+               float* dtopk_w, char* ws, const moe_opts_t& opts, int nw, hipStream_t st);
 }  // namespace uniep
 
 using namespace uniep;
@@ -55,12 +55,13 @@ int check_opts(const moe_opts_t* o, moe_opts_t* out) {
     return MOE_OK;
 }
 
-// Row-tile height: 256 rows when experts average several hundred rows, else 128.
-int pick_fm(const moe_shape_t& s, const moe_opts_t& o) {
-    if (o.tile_rows == 128) return 1;
-    if (o.tile_rows == 256) return 2;
+// Waves per workgroup = row-tile height / 32: 256-row tiles (8 waves, two per
+// SIMD) unless the experts are small.
+int pick_nw(const moe_shape_t& s, const moe_opts_t& o) {
+    if (o.tile_rows == 128) return 4;
+    if (o.tile_rows == 256) return 8;
     const double avg = (double)s.T * s.k / s.E;
-    return avg >= 384.0 ? 2 : 1;
+    return avg >= 160.0 ? 8 : 4;
 }
 
 struct SavedLayout {
@@ -145,7 +146,7 @@ int moe_fused_forward(const moe_shape_t* shape, const void* x, const void* w_gat
         ob = h + align_up(A_cap * shape->I * 2, 256);
     }
     return fwd_launch(*shape, x, w_gate, w_up, w_down, *routing, y, gu, h, ob, wsb, o,
-                      pick_fm(*shape, o), (hipStream_t)stream);
+                      pick_nw(*shape, o), (hipStream_t)stream);
 }
 
 int moe_fused_backward(const moe_shape_t* shape, const void* dy, const void* x, const void* w_gate,
@@ -172,7 +173,7 @@ int moe_fused_backward(const moe_shape_t* shape, const void* dy, const void* x, 
     const SavedLayout L = saved_layout(*shape);
     const char* sv = (const char*)saved;
     return bwd_launch(*shape, dy, x, w_gate, w_up, w_down, *routing, sv + L.gu, sv + L.h, sv + L.o,
-                      dx, dw_gate, dw_up, dw_down, dtopk_w, (char*)ws, o, pick_fm(*shape, o),
+                      dx, dw_gate, dw_up, dw_down, dtopk_w, (char*)ws, o, pick_nw(*shape, o),
                       (hipStream_t)stream);
 }
 

@@ -141,189 +141,192 @@ __global__ void __launch_bounds__(1024) bwd_prologue_kernel(BwdParams p) {
 }
 
 // ------------------------------------------------------------- phase 0: dH
-template <int FM>
+template <int NW>
 __device__ __forceinline__ void dh_task(const BwdParams& p, const RowTile rt, int ct, char* smem) {
+    typedef Geom<NW> G;
     const int d = p.s.d, I = p.s.I;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int mrow = tid >> 3, kc = tid & 7;
-    RowLoader<4 * FM, true> al;
+    const int kc = tid & 7;
+    typedef RowLoader<G::NT, G::BM, true> AL;
+    AL al;
     al.init();
 #pragma unroll
-    for (int q = 0; q < 4 * FM; ++q) {
-        const int row = rt.row0 + min(mrow + 32 * q, rt.rows - 1);
+    for (int q = 0; q < AL::NP; ++q) {
+        const int row = rt.row0 + min(AL::row(q), rt.rows - 1);
         al.rp[q] = p.dy + ((size_t)p.row_tok[row] * d + kc * 8) * 2;
         al.sc[q] = p.row_w[row];
     }
-    RowLoader<8, false> bl;   // B rows are rows of W_down[e]: k (= d) contiguous
+    typedef RowLoader<G::NT, BN, false> BL;   // B rows are rows of W_down[e]: k (= d) contiguous
+    BL bl;
     bl.init();
     const int n0 = ct * BN;
-    {
-        const int c0 = min(n0 + mrow * 8, I - 8);
 #pragma unroll
-        for (int q = 0; q < 8; ++q)
-            bl.rp[q] = p.w_down + (((size_t)rt.expert * I + c0 + q) * d + kc * 8) * 2;
+    for (int q = 0; q < BL::NP; ++q) {
+        const int rho = BL::row(q);                       // LDS row j*32 + nb <-> column nb*8 + j
+        const int c = min(n0 + (rho & 31) * 8, I - 8) + (rho >> 5);
+        bl.rp[q] = p.w_down + (((size_t)rt.expert * I + c) * d + kc * 8) * 2;
     }
-    f32x16_t acc[FM][8];
-    mma_mainloop<FM>(al, bl, d / BK, smem, acc);
+    f32x16_t acc[8];
+    mma_mainloop<NW>(al, bl, d / BK, smem, wave * 32 < rt.rows, acc);
     // epilogue: SwiGLU backward with the saved G, U of the same rows and columns
     const int col = n0 + (lane & 31) * 8;
     if (col < I) {
 #pragma unroll
-        for (int i = 0; i < FM; ++i)
+        for (int v = 0; v < 16; ++v) {
+            const int m = wave * 32 + frag_row(v, lane);
+            if (m < rt.rows) {
+                const size_t base = ((size_t)(rt.row0 + m) * 2 * I + col) * 2;
+                const u32x4_t gv = *(const u32x4_t*)(p.gu + base);
+                const u32x4_t uv = *(const u32x4_t*)(p.gu + base + (size_t)I * 2);
+                float dg[8], du[8];
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int m = (wave * FM + i) * 32 + frag_row(v, lane);
-                if (m < rt.rows) {
-                    const size_t base = ((size_t)(rt.row0 + m) * 2 * I + col) * 2;
-                    const u32x4_t gv = *(const u32x4_t*)(p.gu + base);
-                    const u32x4_t uv = *(const u32x4_t*)(p.gu + base + (size_t)I * 2);
-                    float dg[8], du[8];
-#pragma unroll
-                    for (int f = 0; f < 8; ++f) {
-                        const float g = (f & 1) ? bf16_hi(gv[f >> 1]) : bf16_lo(gv[f >> 1]);
-                        const float u = (f & 1) ? bf16_hi(uv[f >> 1]) : bf16_lo(uv[f >> 1]);
-                        const float dh = acc[i][f][v];
-                        const float sg = sigmoid_f(g);
-                        du[f] = dh * (g * sg);
-                        dg[f] = dh * u * (sg * (1.f + g * (1.f - sg)));
-                    }
-                    u32x4_t dgp, dup;
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        dgp[q] = pack_bf16x2(dg[2 * q], dg[2 * q + 1]);
-                        dup[q] = pack_bf16x2(du[2 * q], du[2 * q + 1]);
-                    }
-                    *(u32x4_t*)(p.dgu + base) = dgp;
-                    *(u32x4_t*)(p.dgu + base + (size_t)I * 2) = dup;
+                for (int f = 0; f < 8; ++f) {
+                    const float g = (f & 1) ? bf16_hi(gv[f >> 1]) : bf16_lo(gv[f >> 1]);
+                    const float u = (f & 1) ? bf16_hi(uv[f >> 1]) : bf16_lo(uv[f >> 1]);
+                    const float dh = acc[f][v];
+                    const float sg = sigmoid_f(g);
+                    du[f] = dh * (g * sg);
+                    dg[f] = dh * u * (sg * (1.f + g * (1.f - sg)));
                 }
+                u32x4_t dgp, dup;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    dgp[q] = pack_bf16x2(dg[2 * q], dg[2 * q + 1]);
+                    dup[q] = pack_bf16x2(du[2 * q], du[2 * q + 1]);
+                }
+                *(u32x4_t*)(p.dgu + base) = dgp;
+                *(u32x4_t*)(p.dgu + base + (size_t)I * 2) = dup;
             }
+        }
     }
 }
 
 // ------------------------------------------------------------- phase 2: dXp
-template <int FM>
+template <int NW>
 __device__ __forceinline__ void dxp_task(const BwdParams& p, const RowTile rt, int ct, char* smem) {
+    typedef Geom<NW> G;
     const int d = p.s.d, I = p.s.I;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int mrow = tid >> 3, kc = tid & 7;
-    RowLoader<4 * FM, false> al;
+    const int kc = tid & 7;
+    typedef RowLoader<G::NT, G::BM, false> AL;
+    AL al;
     al.init();
 #pragma unroll
-    for (int q = 0; q < 4 * FM; ++q) {
-        const int row = rt.row0 + min(mrow + 32 * q, rt.rows - 1);
+    for (int q = 0; q < AL::NP; ++q) {
+        const int row = rt.row0 + min(AL::row(q), rt.rows - 1);
         al.rp[q] = p.dgu + ((size_t)row * 2 * I + kc * 8) * 2;
     }
-    SplitRowLoader<8> bl;   // k < I: row of W_gate[e][dcol], k >= I: row of W_up[e][dcol]
+    typedef SplitRowLoader<G::NT, BN> BL;   // k < I: row of W_gate[e][c], k >= I: row of W_up[e][c]
+    BL bl;
     bl.init();
     const int n0 = ct * BN;
-    {
-        const int c0 = min(n0 + mrow * 8, d - 8);
 #pragma unroll
-        for (int q = 0; q < 8; ++q)
-            bl.rp[q] = p.w_gate + (((size_t)rt.expert * d + c0 + q) * I + kc * 8) * 2;
-        bl.delta = (long long)(p.w_up - p.w_gate);
-        bl.switch_stage = I / BK;
+    for (int q = 0; q < BL::NP; ++q) {
+        const int rho = BL::row(q);
+        const int c = min(n0 + (rho & 31) * 8, d - 8) + (rho >> 5);
+        bl.rp[q] = p.w_gate + (((size_t)rt.expert * d + c) * I + kc * 8) * 2;
     }
-    f32x16_t acc[FM][8];
-    mma_mainloop<FM>(al, bl, 2 * I / BK, smem, acc);
+    bl.delta = (long long)(p.w_up - p.w_gate);
+    bl.switch_stage = I / BK;
+    f32x16_t acc[8];
+    mma_mainloop<NW>(al, bl, 2 * I / BK, smem, wave * 32 < rt.rows, acc);
     const int col = n0 + (lane & 31) * 8;
     if (col < d) {
 #pragma unroll
-        for (int i = 0; i < FM; ++i)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int m = (wave * FM + i) * 32 + frag_row(v, lane);
-                if (m < rt.rows)
-                    *(u32x4_t*)(p.dxp + ((size_t)(rt.row0 + m) * d + col) * 2) = pack_row8<FM>(acc, i, v);
-            }
+        for (int v = 0; v < 16; ++v) {
+            const int m = wave * 32 + frag_row(v, lane);
+            if (m < rt.rows)
+                *(u32x4_t*)(p.dxp + ((size_t)(rt.row0 + m) * d + col) * 2) = pack_row8(acc, v);
+        }
     }
-}
-
-// Output row (within the 256-row tile) of accumulator (fragment i, element v)
-// when the A operand went through a transposing loader: LDS row j*32+mb holds
-// m = mb*8 + j, wave w reads rows [64w, 64w+64), so j = 2w+i and mb = frag row.
-__device__ __forceinline__ int tr_out_row(int wave, int i, int v, int lane) {
-    return frag_row(v, lane) * 8 + 2 * wave + i;
 }
 
 // ------------------------------------------------------------- phase 1: dW_down
 // dW_down[e][i][c] = sum over the expert's rows r (ascending) of h[r][i] * dO[r][c].
+// Output tile: 32*NW rows of I by 256 columns of d.
+template <int NW>
 __device__ __forceinline__ void dwd_task(const BwdParams& p, int e, int mt, int nt, char* smem) {
+    typedef Geom<NW> G;
     const int d = p.s.d, I = p.s.I;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int r0 = p.offsets[e], cnt = p.offsets[e + 1] - r0;
-    const int cb = tid & 31;
-    StridedLoaderK al;
+    typedef StridedLoaderK<G::NT, 4 * NW> AL;
+    AL al;
     al.init();
     al.ld_bytes = (size_t)I * 2;
     al.K = cnt;
-    al.bp = p.h + ((size_t)r0 * I + min(mt * 256 + cb * 8, I - 8)) * 2;
-    GatherStridedLoader<true> bl;
+    al.bp = p.h + ((size_t)r0 * I + min(mt * G::BM + AL::TG::chunk() * 8, I - 8)) * 2;
+    typedef GatherStridedLoader<G::NT, 32, true> BL;
+    BL bl;
     bl.init();
     bl.ld_bytes = (size_t)d * 2;
     bl.row_tok = p.row_tok;
     bl.row_w = p.row_w;
     bl.row0 = r0;
     bl.K = cnt;
-    bl.src = p.dy + (size_t)min(nt * 256 + cb * 8, d - 8) * 2;
-    f32x16_t acc[2][8];
-    mma_mainloop<2>(al, bl, (cnt + BK - 1) / BK, smem, acc);
-    const int col = nt * 256 + (lane & 31) * 8;
+    bl.src = p.dy + (size_t)min(nt * BN + BL::TG::chunk() * 8, d - 8) * 2;
+    f32x16_t acc[8];
+    mma_mainloop<NW>(al, bl, (cnt + BK - 1) / BK, smem, true, acc);
+    const int col = nt * BN + (lane & 31) * 8;
     if (col < d) {
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int m = mt * 256 + tr_out_row(wave, i, v, lane);
-                if (m < I)
-                    *(u32x4_t*)(p.dw_down + (((size_t)e * I + m) * d + col) * 2) = pack_row8<2>(acc, i, v);
-            }
+        for (int v = 0; v < 16; ++v) {
+            const int m = mt * G::BM + tr_tile_row<NW>(wave * 32 + frag_row(v, lane));
+            if (m < I)
+                *(u32x4_t*)(p.dw_down + (((size_t)e * I + m) * d + col) * 2) = pack_row8(acc, v);
+        }
     }
 }
 
 // ------------------------------------------------------------- phase 3: dW_gate, dW_up
 // dW_gate[e][c][i] = sum_r x[tok(r)][c] * dG[r][i]; dW_up likewise with dU.
+// Output tile: 32*NW rows of d by 128 columns of I, for both matrices at once.
 // B-tile chunk nb: even -> 8 columns of dG, odd -> the same 8 columns of dU.
+template <int NW>
 __device__ __forceinline__ void dwgu_task(const BwdParams& p, int e, int mt, int nt, char* smem) {
+    typedef Geom<NW> G;
     const int d = p.s.d, I = p.s.I;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int r0 = p.offsets[e], cnt = p.offsets[e + 1] - r0;
-    const int cb = tid & 31;
-    GatherStridedLoader<false> al;
+    typedef GatherStridedLoader<G::NT, 4 * NW, false> AL;
+    AL al;
     al.init();
     al.ld_bytes = (size_t)d * 2;
     al.row_tok = p.row_tok;
     al.row_w = p.row_w;
     al.row0 = r0;
     al.K = cnt;
-    al.src = p.x + (size_t)min(mt * 256 + cb * 8, d - 8) * 2;
-    StridedLoaderK bl;
+    al.src = p.x + (size_t)min(mt * G::BM + AL::TG::chunk() * 8, d - 8) * 2;
+    typedef StridedLoaderK<G::NT, 32> BL;
+    BL bl;
     bl.init();
     bl.ld_bytes = (size_t)I * 4;
     bl.K = cnt;
-    bl.bp = p.dgu + ((size_t)r0 * 2 * I + ((cb & 1) ? I : 0) + min(nt * 128 + (cb >> 1) * 8, I - 8)) * 2;
-    f32x16_t acc[2][8];
-    mma_mainloop<2>(al, bl, (cnt + BK - 1) / BK, smem, acc);
+    {
+        const int cb = BL::TG::chunk();
+        bl.bp = p.dgu + ((size_t)r0 * 2 * I + ((cb & 1) ? I : 0) + min(nt * 128 + (cb >> 1) * 8, I - 8)) * 2;
+    }
+    f32x16_t acc[8];
+    mma_mainloop<NW>(al, bl, (cnt + BK - 1) / BK, smem, true, acc);
     const int nb = lane & 31;
     const int icol = nt * 128 + (nb >> 1) * 8;
     char* dst = (nb & 1) ? p.dw_up : p.dw_gate;
     if (icol < I) {
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int m = mt * 256 + tr_out_row(wave, i, v, lane);
-                if (m < d)
-                    *(u32x4_t*)(dst + (((size_t)e * d + m) * I + icol) * 2) = pack_row8<2>(acc, i, v);
-            }
+        for (int v = 0; v < 16; ++v) {
+            const int m = mt * G::BM + tr_tile_row<NW>(wave * 32 + frag_row(v, lane));
+            if (m < d)
+                *(u32x4_t*)(dst + (((size_t)e * d + m) * I + icol) * 2) = pack_row8(acc, v);
+        }
     }
 }
 
 // ------------------------------------------------------------- phase 4: dX, dtopk_w
+template <int NW>
 __device__ __forceinline__ void dx_task(const BwdParams& p, int block) {
     const int d = p.s.d, k = p.s.k, T = p.s.T;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    for (int tt = wave; tt < kDxTokens; tt += 4) {
+    for (int tt = wave; tt < kDxTokens; tt += NW) {
         const int t = block * kDxTokens + tt;
         if (t >= T) break;
         int rows[kMaxTopK];
@@ -375,8 +378,8 @@ __device__ __forceinline__ void dx_task(const BwdParams& p, int block) {
 }
 
 // ------------------------------------------------------------- worker loop
-template <int FM>
-__global__ void __launch_bounds__(kTileThreads) __attribute__((amdgpu_waves_per_eu(1, 1)))
+template <int NW>
+__global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW / 4, NW / 4)))
 bwd_worker_kernel(BwdParams p, int phase) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     __shared__ int s_task;
@@ -394,20 +397,20 @@ bwd_worker_kernel(BwdParams p, int phase) {
         const int type = task.type_ct >> 20, ct = task.type_ct & 0xfffff;
         if (type == B_DH) {
             const RowTile rt = p.rt[task.rt];
-            dh_task<FM>(p, rt, ct, smem);
+            dh_task<NW>(p, rt, ct, smem);
             __syncthreads();
             if (threadIdx.x == 0) {
                 add_release(p.flag_rt + task.rt, 1);
                 add_release(p.flag_e + rt.expert, 1);
             }
         } else if (type == B_DWD) {
-            dwd_task(p, task.rt / p.mt_dwd, task.rt % p.mt_dwd, ct, smem);
+            dwd_task<NW>(p, task.rt / p.mt_dwd, task.rt % p.mt_dwd, ct, smem);
         } else if (type == B_DXP) {
             if (threadIdx.x == 0) s_ok = wait_ge(p.flag_rt + task.rt, p.nct_dh, ctrl, p.spin_ticks);
             __syncthreads();
             if (s_ok) {
                 const RowTile rt = p.rt[task.rt];
-                dxp_task<FM>(p, rt, ct, smem);
+                dxp_task<NW>(p, rt, ct, smem);
             }
             __syncthreads();
             if (threadIdx.x == 0) add_release(ctrl + CTRL_DONE + 2, 1);
@@ -415,11 +418,11 @@ bwd_worker_kernel(BwdParams p, int phase) {
             const int e = task.rt / p.mt_dwgu;
             if (threadIdx.x == 0) s_ok = wait_ge(p.flag_e + e, p.need_e[e], ctrl, p.spin_ticks);
             __syncthreads();
-            if (s_ok) dwgu_task(p, e, task.rt % p.mt_dwgu, ct, smem);
+            if (s_ok) dwgu_task<NW>(p, e, task.rt % p.mt_dwgu, ct, smem);
         } else {
             if (threadIdx.x == 0) s_ok = wait_ge(ctrl + CTRL_DONE + 2, n_dxp, ctrl, p.spin_ticks);
             __syncthreads();
-            if (s_ok) dx_task(p, task.rt);
+            if (s_ok) dx_task<NW>(p, task.rt);
         }
         __syncthreads();
     }
@@ -432,15 +435,15 @@ struct BwdLayout {
     int max_rt, nct_dh, nct_dxp, mt_dwd, nt_dwd, mt_dwgu, nt_dwgu;
 };
 
-static BwdLayout bwd_layout(const moe_shape_t& s) {
+static BwdLayout bwd_layout(const moe_shape_t& s, int bm) {
     BwdLayout L;
     const size_t A_cap = (size_t)s.T * s.k;
     L.max_rt = (int)((A_cap + 127) / 128) + s.e_count;
     L.nct_dh = (s.I + BN - 1) / BN;
     L.nct_dxp = (s.d + BN - 1) / BN;
-    L.mt_dwd = (s.I + 255) / 256;
+    L.mt_dwd = (s.I + bm - 1) / bm;
     L.nt_dwd = (s.d + 255) / 256;
-    L.mt_dwgu = (s.d + 255) / 256;
+    L.mt_dwgu = (s.d + bm - 1) / bm;
     L.nt_dwgu = (s.I + 127) / 128;
     const size_t max_tasks = (size_t)L.max_rt * (L.nct_dh + L.nct_dxp) +
                              (size_t)s.e_count * (L.mt_dwd * L.nt_dwd + L.mt_dwgu * L.nt_dwgu) +
@@ -460,23 +463,23 @@ static BwdLayout bwd_layout(const moe_shape_t& s) {
     return L;
 }
 
-size_t bwd_workspace_bytes(const moe_shape_t& s) { return bwd_layout(s).total; }
+size_t bwd_workspace_bytes(const moe_shape_t& s) { return bwd_layout(s, 128).total; }   // 128-row tiles need the most tasks
 
 static int g_bwd_workers[16];
 
-template <int FM>
+template <int NW>
 static int bwd_resident_workers(int* out) {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess) return MOE_ERR_HIP;
-    const int slot = (dev & 7) * 2 + (FM - 1);
+    const int slot = (dev & 7) * 2 + (NW == 8 ? 1 : 0);
     if (g_bwd_workers[slot] == 0) {
-        if (hipFuncSetAttribute((const void*)bwd_worker_kernel<FM>,
+        if (hipFuncSetAttribute((const void*)bwd_worker_kernel<NW>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize,
-                                Geom<2>::SMEM) != hipSuccess)
+                                Geom<NW>::SMEM) != hipSuccess)
             return MOE_ERR_HIP;
         int per_cu = 0, cus = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, bwd_worker_kernel<FM>, kTileThreads,
-                                                         Geom<2>::SMEM) != hipSuccess)
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, bwd_worker_kernel<NW>, Geom<NW>::NT,
+                                                         Geom<NW>::SMEM) != hipSuccess)
             return MOE_ERR_HIP;
         if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
             return MOE_ERR_HIP;
@@ -487,22 +490,22 @@ static int bwd_resident_workers(int* out) {
     return MOE_OK;
 }
 
-template <int FM>
-static int bwd_launch_fm(BwdParams& p, const moe_opts_t& opts, hipStream_t st) {
+template <int NW>
+static int bwd_launch_nw(BwdParams& p, const moe_opts_t& opts, hipStream_t st) {
     int resident = 0;
-    int rc = bwd_resident_workers<FM>(&resident);
+    int rc = bwd_resident_workers<NW>(&resident);
     if (rc != MOE_OK) return rc;
     const int workers = opts.workers > 0 ? min(opts.workers, resident) : resident;
     const int A_cap = p.s.T * p.s.k;
     if (A_cap > 0)
         hipLaunchKernelGGL(row_meta_kernel, dim3((A_cap + 255) / 256), dim3(256), 0, st, p);
-    hipLaunchKernelGGL(bwd_prologue_kernel<Geom<FM>::BM>, dim3(1), dim3(1024), 0, st, p);
+    hipLaunchKernelGGL(bwd_prologue_kernel<Geom<NW>::BM>, dim3(1), dim3(1024), 0, st, p);
     if (opts.schedule == 2) {
         for (int phase = 0; phase < 5; ++phase)
-            hipLaunchKernelGGL(bwd_worker_kernel<FM>, dim3(workers), dim3(kTileThreads),
-                               Geom<2>::SMEM, st, p, phase);
+            hipLaunchKernelGGL(bwd_worker_kernel<NW>, dim3(workers), dim3(Geom<NW>::NT),
+                               Geom<NW>::SMEM, st, p, phase);
     } else {
-        hipLaunchKernelGGL(bwd_worker_kernel<FM>, dim3(workers), dim3(kTileThreads), Geom<2>::SMEM,
+        hipLaunchKernelGGL(bwd_worker_kernel<NW>, dim3(workers), dim3(Geom<NW>::NT), Geom<NW>::SMEM,
                            st, p, -1);
     }
     return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
@@ -511,8 +514,8 @@ static int bwd_launch_fm(BwdParams& p, const moe_opts_t& opts, hipStream_t st) {
 int bwd_launch(const moe_shape_t& s, const void* dy, const void* x, const void* w_gate,
                const void* w_up, const void* w_down, const moe_routing_t& r, const char* gu,
                const char* h, const char* o, void* dx, void* dw_gate, void* dw_up, void* dw_down,
-               float* dtopk_w, char* ws, const moe_opts_t& opts, int fm, hipStream_t st) {
-    const BwdLayout L = bwd_layout(s);
+               float* dtopk_w, char* ws, const moe_opts_t& opts, int nw, hipStream_t st) {
+    const BwdLayout L = bwd_layout(s, 32 * nw);
     BwdParams p;
     p.s = s;
     p.dy = (const char*)dy;
@@ -550,7 +553,7 @@ int bwd_launch(const moe_shape_t& s, const void* dy, const void* x, const void* 
     p.nt_dwgu = L.nt_dwgu;
     const int ms = opts.spin_limit_ms > 0 ? opts.spin_limit_ms : 2000;
     p.spin_ticks = (long long)ms * 100000ll;
-    return fm == 1 ? bwd_launch_fm<1>(p, opts, st) : bwd_launch_fm<2>(p, opts, st);
+    return nw == 4 ? bwd_launch_nw<4>(p, opts, st) : bwd_launch_nw<8>(p, opts, st);
 }
 
 }  // namespace uniep

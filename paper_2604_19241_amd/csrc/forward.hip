@@ -99,34 +99,37 @@ __global__ void __launch_bounds__(1024) fwd_prologue_kernel(FwdParams p) {
 // h[row0.., ct*128 .. +128) = silu(x_e W_gate) * (x_e W_up) for one row tile.
 // B-tile chunk nb: even -> 8 gate columns, odd -> the same 8 up columns, so the
 // lanes 2q and 2q+1 hold G and U of the same columns.
-template <int FM>
+template <int NW>
 __device__ __forceinline__ void gemm1_task(const FwdParams& p, const RowTile rt, int ct,
                                            char* smem) {
+    typedef Geom<NW> G;
     const int d = p.s.d, I = p.s.I, k = p.s.k;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    RowLoader<4 * FM, false> al;
+    typedef RowLoader<G::NT, G::BM, false> AL;
+    AL al;
     al.init();
     {
-        const int mrow = tid >> 3, kc = tid & 7;
+        const int kc = tid & 7;
 #pragma unroll
-        for (int q = 0; q < 4 * FM; ++q) {
-            const int m = min(mrow + 32 * q, rt.rows - 1);   // rows past the tile alias its last row
+        for (int q = 0; q < AL::NP; ++q) {
+            const int m = min(AL::row(q), rt.rows - 1);   // rows past the tile alias its last row
             const int tok = p.perm[rt.row0 + m] / k;
             al.rp[q] = p.x + ((size_t)tok * d + kc * 8) * 2;
         }
     }
-    StridedLoader bl;
+    typedef StridedLoader<G::NT, 32> BL;
+    BL bl;
     bl.init();
     const int n0h = ct * (BN / 2);
     {
-        const int nb = tid & 31, kb = tid >> 5;
+        const int nb = BL::TG::chunk();
         const int hc = min(n0h + (nb >> 1) * 8, I - 8);   // chunks past I alias the last chunk
         const char* w = (nb & 1) ? p.w_up : p.w_gate;
         bl.ld_bytes = (size_t)I * 2;
-        bl.bp = w + (((size_t)rt.expert * d + kb * 8) * I + hc) * 2;
+        bl.bp = w + (((size_t)rt.expert * d + BL::TG::k0()) * I + hc) * 2;
     }
-    f32x16_t acc[FM][8];
-    mma_mainloop<FM>(al, bl, d / BK, smem, acc);
+    f32x16_t acc[8];
+    mma_mainloop<NW>(al, bl, d / BK, smem, wave * 32 < rt.rows, acc);
 
     // epilogue: SwiGLU on the accumulators; lanes (2q, 2q+1) trade halves so that
     // each ends with G and U of 4 consecutive h-columns.
@@ -136,80 +139,75 @@ __device__ __forceinline__ void gemm1_task(const FwdParams& p, const RowTile rt,
     const int gcol = n0h + (nb >> 1) * 8;       // first of the 8 G (even) / U (odd) columns
     const bool col_ok = gcol < I;
 #pragma unroll
-    for (int i = 0; i < FM; ++i) {
+    for (int v = 0; v < 16; ++v) {
+        const int m = wave * 32 + frag_row(v, lane);
+        float hv[4];
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int m = (wave * FM + i) * 32 + frag_row(v, lane);
-            float hv[4];
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const float mine_lo = acc[i][q][v], mine_hi = acc[i][q + 4][v];
-                const float recv = dpp_swap_pair(odd ? mine_lo : mine_hi);
-                const float g = odd ? recv : mine_lo;
-                const float u = odd ? mine_hi : recv;
-                hv[q] = g * sigmoid_f(g) * u;
-            }
-            if (m < rt.rows && col_ok) {
-                const size_t row = (size_t)(rt.row0 + m);
-                u32x2_t hp = {pack_bf16x2(hv[0], hv[1]), pack_bf16x2(hv[2], hv[3])};
-                *(u32x2_t*)(p.h + (row * I + hcol) * 2) = hp;
-                if (p.gu) {
-                    const u32x4_t guv = pack_row8<FM>(acc, i, v);
-                    *(u32x4_t*)(p.gu + (row * 2 * I + (odd ? I : 0) + gcol) * 2) = guv;
-                }
-            }
+        for (int q = 0; q < 4; ++q) {
+            const float mine_lo = acc[q][v], mine_hi = acc[q + 4][v];
+            const float recv = dpp_swap_pair(odd ? mine_lo : mine_hi);
+            const float g = odd ? recv : mine_lo;
+            const float u = odd ? mine_hi : recv;
+            hv[q] = g * sigmoid_f(g) * u;
+        }
+        if (m < rt.rows && col_ok) {
+            const size_t row = (size_t)(rt.row0 + m);
+            u32x2_t hp = {pack_bf16x2(hv[0], hv[1]), pack_bf16x2(hv[2], hv[3])};
+            *(u32x2_t*)(p.h + (row * I + hcol) * 2) = hp;
+            if (p.gu) *(u32x4_t*)(p.gu + (row * 2 * I + (odd ? I : 0) + gcol) * 2) = pack_row8(acc, v);
         }
     }
 }
 
 // ------------------------------------------------------------- GEMM2 task
 // o[row0.., ct*256 .. +256) = h_e W_down[e] for one row tile.
-template <int FM>
+template <int NW>
 __device__ __forceinline__ void gemm2_task(const FwdParams& p, const RowTile rt, int ct,
                                            char* smem) {
+    typedef Geom<NW> G;
     const int d = p.s.d, I = p.s.I;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    RowLoader<4 * FM, false> al;
+    typedef RowLoader<G::NT, G::BM, false> AL;
+    AL al;
     al.init();
     {
-        const int mrow = tid >> 3, kc = tid & 7;
+        const int kc = tid & 7;
 #pragma unroll
-        for (int q = 0; q < 4 * FM; ++q) {
-            const int m = min(mrow + 32 * q, rt.rows - 1);
+        for (int q = 0; q < AL::NP; ++q) {
+            const int m = min(AL::row(q), rt.rows - 1);
             al.rp[q] = p.h + ((size_t)(rt.row0 + m) * I + kc * 8) * 2;
         }
     }
-    StridedLoader bl;
+    typedef StridedLoader<G::NT, 32> BL;
+    BL bl;
     bl.init();
     const int n0 = ct * BN;
     {
-        const int nb = tid & 31, kb = tid >> 5;
-        const int c = min(n0 + nb * 8, d - 8);
+        const int c = min(n0 + BL::TG::chunk() * 8, d - 8);
         bl.ld_bytes = (size_t)d * 2;
-        bl.bp = p.w_down + (((size_t)rt.expert * I + kb * 8) * d + c) * 2;
+        bl.bp = p.w_down + (((size_t)rt.expert * I + BL::TG::k0()) * d + c) * 2;
     }
-    f32x16_t acc[FM][8];
-    mma_mainloop<FM>(al, bl, I / BK, smem, acc);
+    f32x16_t acc[8];
+    mma_mainloop<NW>(al, bl, I / BK, smem, wave * 32 < rt.rows, acc);
     const int col = n0 + (lane & 31) * 8;
     if (col < d) {
 #pragma unroll
-        for (int i = 0; i < FM; ++i)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int m = (wave * FM + i) * 32 + frag_row(v, lane);
-                if (m < rt.rows)
-                    *(u32x4_t*)(p.o + ((size_t)(rt.row0 + m) * d + col) * 2) = pack_row8<FM>(acc, i, v);
-            }
+        for (int v = 0; v < 16; ++v) {
+            const int m = wave * 32 + frag_row(v, lane);
+            if (m < rt.rows)
+                *(u32x4_t*)(p.o + ((size_t)(rt.row0 + m) * d + col) * 2) = pack_row8(acc, v);
+        }
     }
 }
 
 // ------------------------------------------------------------- combine task
 // y[t] = sum_j w[t,j] * o[row(t,j)], slot order, fp32; one wave per token, 16
 // bytes per lane, no LDS (Section 5.2 "Relay & Reduce Workers").
+template <int NW>
 __device__ __forceinline__ void combine_task(const FwdParams& p, int block) {
     const int d = p.s.d, k = p.s.k, T = p.s.T;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    for (int tt = wave; tt < kCombineTokens; tt += 4) {
+    for (int tt = wave; tt < kCombineTokens; tt += NW) {
         const int t = block * kCombineTokens + tt;
         if (t >= T) break;
         int rows[kMaxTopK];
@@ -246,8 +244,8 @@ __device__ __forceinline__ void combine_task(const FwdParams& p, int block) {
 // phase < 0: the whole queue with scoreboard waits (persistent MegaKernel).
 // phase >= 0: only that phase's tasks (staged schedule; the waits are already
 // satisfied by stream order).
-template <int FM>
-__global__ void __launch_bounds__(kTileThreads) __attribute__((amdgpu_waves_per_eu(1, 1)))
+template <int NW>
+__global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW / 4, NW / 4)))
 fwd_worker_kernel(FwdParams p, int phase) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     __shared__ int s_task;
@@ -265,7 +263,7 @@ fwd_worker_kernel(FwdParams p, int phase) {
         const int type = task.type_ct >> 20, ct = task.type_ct & 0xfffff;
         if (type == TASK_GEMM1) {
             const RowTile rt = p.rt[task.rt];
-            gemm1_task<FM>(p, rt, ct, smem);
+            gemm1_task<NW>(p, rt, ct, smem);
             __syncthreads();   // all h stores of the tile issued and complete at workgroup scope
             if (threadIdx.x == 0) add_release(p.flag1 + task.rt, 1);
         } else if (type == TASK_GEMM2) {
@@ -273,14 +271,14 @@ fwd_worker_kernel(FwdParams p, int phase) {
             __syncthreads();
             if (s_ok) {
                 const RowTile rt = p.rt[task.rt];
-                gemm2_task<FM>(p, rt, ct, smem);
+                gemm2_task<NW>(p, rt, ct, smem);
             }
             __syncthreads();
             if (threadIdx.x == 0) add_release(ctrl + CTRL_DONE + 1, 1);
         } else {
             if (threadIdx.x == 0) s_ok = wait_ge(ctrl + CTRL_DONE + 1, n2_total, ctrl, p.spin_ticks);
             __syncthreads();
-            if (s_ok) combine_task(p, task.rt);
+            if (s_ok) combine_task<NW>(p, task.rt);
         }
         __syncthreads();   // s_task / s_ok are rewritten next round
     }
@@ -315,21 +313,21 @@ FwdLayout fwd_layout(const moe_shape_t& s, bool with_ho) {
 size_t fwd_workspace_bytes(const moe_shape_t& s) { return fwd_layout(s, true).total; }
 size_t fwd_ctrl_bytes(const moe_shape_t& s) { return fwd_layout(s, false).total; }
 
-static int g_workers[16];   // resident worker slots per device, per FM (index dev*2 + FM-1)
+static int g_workers[16];   // resident worker slots per device and tile height
 
-template <int FM>
+template <int NW>
 static int resident_workers(int* out) {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess) return MOE_ERR_HIP;
-    const int slot = (dev & 7) * 2 + (FM - 1);
+    const int slot = (dev & 7) * 2 + (NW == 8 ? 1 : 0);
     if (g_workers[slot] == 0) {
-        if (hipFuncSetAttribute((const void*)fwd_worker_kernel<FM>,
+        if (hipFuncSetAttribute((const void*)fwd_worker_kernel<NW>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize,
-                                Geom<FM>::SMEM) != hipSuccess)
+                                Geom<NW>::SMEM) != hipSuccess)
             return MOE_ERR_HIP;
         int per_cu = 0, cus = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fwd_worker_kernel<FM>,
-                                                         kTileThreads, Geom<FM>::SMEM) != hipSuccess)
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fwd_worker_kernel<NW>,
+                                                         Geom<NW>::NT, Geom<NW>::SMEM) != hipSuccess)
             return MOE_ERR_HIP;
         if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
             return MOE_ERR_HIP;
@@ -340,27 +338,27 @@ static int resident_workers(int* out) {
     return MOE_OK;
 }
 
-template <int FM>
-static int fwd_launch_fm(FwdParams& p, const moe_opts_t& opts, hipStream_t st) {
+template <int NW>
+static int fwd_launch_nw(FwdParams& p, const moe_opts_t& opts, hipStream_t st) {
     int resident = 0;
-    int rc = resident_workers<FM>(&resident);
+    int rc = resident_workers<NW>(&resident);
     if (rc != MOE_OK) return rc;
     int workers = opts.workers > 0 ? min(opts.workers, resident) : resident;
-    hipLaunchKernelGGL(fwd_prologue_kernel<Geom<FM>::BM>, dim3(1), dim3(1024), 0, st, p);
+    hipLaunchKernelGGL(fwd_prologue_kernel<Geom<NW>::BM>, dim3(1), dim3(1024), 0, st, p);
     if (opts.schedule == 2) {
         for (int phase = 0; phase < 3; ++phase)
-            hipLaunchKernelGGL(fwd_worker_kernel<FM>, dim3(workers), dim3(kTileThreads),
-                               Geom<FM>::SMEM, st, p, phase);
+            hipLaunchKernelGGL(fwd_worker_kernel<NW>, dim3(workers), dim3(Geom<NW>::NT),
+                               Geom<NW>::SMEM, st, p, phase);
     } else {
-        hipLaunchKernelGGL(fwd_worker_kernel<FM>, dim3(workers), dim3(kTileThreads),
-                           Geom<FM>::SMEM, st, p, -1);
+        hipLaunchKernelGGL(fwd_worker_kernel<NW>, dim3(workers), dim3(Geom<NW>::NT),
+                           Geom<NW>::SMEM, st, p, -1);
     }
     return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
 
 int fwd_launch(const moe_shape_t& s, const void* x, const void* w_gate, const void* w_up,
                const void* w_down, const moe_routing_t& r, void* y, char* gu, char* h, char* o,
-               char* ws, const moe_opts_t& opts, int fm, hipStream_t st) {
+               char* ws, const moe_opts_t& opts, int nw, hipStream_t st) {
     const FwdLayout L = fwd_layout(s, false);
     FwdParams p;
     p.s = s;
@@ -385,7 +383,7 @@ int fwd_launch(const moe_shape_t& s, const void* x, const void* w_gate, const vo
     p.max_rt = L.max_rt;
     const int ms = opts.spin_limit_ms > 0 ? opts.spin_limit_ms : 2000;
     p.spin_ticks = (long long)ms * 100000ll;   // wall_clock64 ticks at 100 MHz
-    return fm == 1 ? fwd_launch_fm<1>(p, opts, st) : fwd_launch_fm<2>(p, opts, st);
+    return nw == 4 ? fwd_launch_nw<4>(p, opts, st) : fwd_launch_nw<8>(p, opts, st);
 }
 
 }  // namespace uniep

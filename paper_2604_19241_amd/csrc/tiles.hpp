@@ -1,8 +1,10 @@
 // bf16 MFMA tile machinery for gfx950 (CDNA4), shared by forward and backward.
 //
-// A workgroup is 4 waves (256 threads) and owns an output tile of BM = 128*FM
-// rows by BN = 256 columns; wave w owns rows [w*32*FM, (w+1)*32*FM) and all 256
-// columns (FM x 8 accumulators of v_mfma_f32_32x32x16_bf16, 16 fp32 each).
+// A workgroup is NW waves (NW = 8: two waves per SIMD, or NW = 4) and owns an
+// output tile of BM = 32*NW rows by BN = 256 columns; wave w owns rows
+// [32w, 32w+32) and all 256 columns: 8 accumulators of
+// v_mfma_f32_32x32x16_bf16 (16 fp32 each, kept in AGPRs).  With NW = 8 the two
+// waves of a SIMD hide each other's LDS and global latency.
 // Both operands are staged through LDS as [row][k] with k contiguous, 64 k per
 // stage, rows padded to 144 bytes so that 16-byte fragment reads of
 // consecutive rows fall in distinct banks.  Two LDS stages: global loads of
@@ -12,8 +14,8 @@
 // consecutive columns.  Column (chunk nb, j) lives in LDS row j*32 + nb, so B
 // fragment f of lane c is column c*8 + f: after the main loop a lane holds 8
 // consecutive output columns of each of its rows and stores them as one
-// 16-byte vector, and a loader thread that transposed an 8x8 block writes 8
-// rows that are consecutive across lanes (bank-conflict free).
+// 16-byte vector, and a loader thread that transposed a block of k-rows x 8
+// columns writes LDS rows that are consecutive across lanes (conflict free).
 #pragma once
 #include "common.hpp"
 
@@ -22,11 +24,11 @@ namespace uniep {
 constexpr int BK = 64;
 constexpr int BN = 256;
 constexpr int kRowBytes = (BK + 8) * 2;   // 144
-constexpr int kTileThreads = 256;
 
-template <int FM>
+template <int NW>
 struct Geom {
-    static constexpr int BM = 128 * FM;
+    static constexpr int NT = 64 * NW;        // threads
+    static constexpr int BM = 32 * NW;        // tile rows
     static constexpr int A_BYTES = BM * kRowBytes;
     static constexpr int B_BYTES = BN * kRowBytes;
     static constexpr int STAGE = A_BYTES + B_BYTES;
@@ -44,90 +46,53 @@ __device__ __forceinline__ u32x4_t zero4() { return u32x4_t{0u, 0u, 0u, 0u}; }
 // Every loader has  gload(s): fetch K-stage s into registers, and
 // sstore(base): write those registers into the operand's LDS region.
 
-// Rows with k contiguous in memory (activations).  Thread (mrow = tid/8,
-// kc = tid%8) moves the 16-byte piece kc of rows mrow, mrow+32, ...: eight
-// neighbouring lanes read 128 contiguous bytes of one row.  rp[p] points at
-// that piece for stage 0 and must always be readable: rows beyond the tile
-// alias a valid row (their products land in output rows that are never stored).
+// Rows with k contiguous in memory.  Thread (tid/8, tid%8) moves the 16-byte
+// piece tid%8 of LDS rows tid/8 + p*NT/8: eight neighbouring lanes read 128
+// contiguous bytes of one row.  rp[p] points at that piece for stage 0 and must
+// always be readable: rows beyond the tile alias a valid row (their products
+// land in outputs that are never stored).
 // SCALE: multiply the row by a per-row fp32 factor and round to bf16 once.
-template <int NROWS32, bool SCALE>
+template <int NT, int NROWS, bool SCALE>
 struct RowLoader {
-    const char* rp[NROWS32];
-    float sc[NROWS32];
-    u32x4_t reg[NROWS32];
-    int lds_off;   // (tid/8)*144 + (tid%8)*16
+    static constexpr int RPP = NT / 8;         // rows per pass
+    static constexpr int NP = NROWS / RPP;     // passes
+    const char* rp[NP];
+    float sc[NP];
+    u32x4_t reg[NP];
+    int lds_off;
 
     __device__ __forceinline__ void init() {
         lds_off = (threadIdx.x >> 3) * kRowBytes + (threadIdx.x & 7) * 16;
     }
+    // LDS row that pass p of this thread fills
+    static __device__ __forceinline__ int row(int p) { return (threadIdx.x >> 3) + p * RPP; }
     __device__ __forceinline__ void gload(int s) {
 #pragma unroll
-        for (int p = 0; p < NROWS32; ++p)
-            reg[p] = *(const u32x4_t*)(rp[p] + (size_t)s * (BK * 2));
+        for (int p = 0; p < NP; ++p) reg[p] = *(const u32x4_t*)(rp[p] + (size_t)s * (BK * 2));
     }
     __device__ __forceinline__ void sstore(char* base) {
 #pragma unroll
-        for (int p = 0; p < NROWS32; ++p) {
+        for (int p = 0; p < NP; ++p) {
             u32x4_t r = reg[p];
             if (SCALE) {
                 const float f = sc[p];
 #pragma unroll
                 for (int q = 0; q < 4; ++q) r[q] = pack_bf16x2(bf16_lo(r[q]) * f, bf16_hi(r[q]) * f);
             }
-            *(u32x4_t*)(base + lds_off + p * 32 * kRowBytes) = r;
+            *(u32x4_t*)(base + lds_off + p * RPP * kRowBytes) = r;
         }
-    }
-};
-
-// 8x8 bf16 transpose in registers: in[r] = 8 consecutive columns of k-row r;
-// out[j] = the 8 k-values of column j, k ascending.
-__device__ __forceinline__ void transpose8x8(const u32x4_t (&in)[8], u32x4_t (&out)[8]) {
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-#pragma unroll
-        for (int p = 0; p < 4; ++p) {
-            const uint32_t lo = in[2 * p][j >> 1], hi = in[2 * p + 1][j >> 1];
-            out[j][p] = (j & 1) ? ((lo >> 16) | (hi & 0xffff0000u)) : ((lo & 0xffffu) | (hi << 16));
-        }
-    }
-}
-
-// Operand whose k runs along memory rows (row pitch ld_bytes) and whose tile
-// "rows" (the M or N index) are contiguous in memory: weights [K,N] in the
-// forward pass.  Thread (kb = tid/32, nb = tid%32) fetches the 8x8 block
-// k in [kb*8, kb*8+8) x chunk nb, transposes it in registers and writes 8
-// LDS rows j*32 + nb.  bp = address of (k = kb*8 of stage 0, first column of
-// chunk nb); chunks outside the matrix alias a valid chunk (their output
-// columns are never stored).
-struct StridedLoader {
-    const char* bp;
-    size_t ld_bytes;
-    u32x4_t reg[8];
-    int lds_off;   // nb*144 + kb*16
-
-    __device__ __forceinline__ void init() {
-        lds_off = (threadIdx.x & 31) * kRowBytes + (threadIdx.x >> 5) * 16;
-    }
-    __device__ __forceinline__ void gload(int s) {
-        const char* p = bp + (size_t)s * BK * ld_bytes;
-#pragma unroll
-        for (int r = 0; r < 8; ++r) reg[r] = *(const u32x4_t*)(p + r * ld_bytes);
-    }
-    __device__ __forceinline__ void sstore(char* base) {
-        u32x4_t out[8];
-        transpose8x8(reg, out);
-#pragma unroll
-        for (int j = 0; j < 8; ++j) *(u32x4_t*)(base + lds_off + j * 32 * kRowBytes) = out[j];
     }
 };
 
 // RowLoader whose k axis is the concatenation of two matrices with identical
 // layout (W_gate then W_up along k): stages >= switch_stage read from the
 // second matrix, which sits `delta` bytes after the first.
-template <int NROWS32>
+template <int NT, int NROWS>
 struct SplitRowLoader {
-    const char* rp[NROWS32];
-    u32x4_t reg[NROWS32];
+    static constexpr int RPP = NT / 8;
+    static constexpr int NP = NROWS / RPP;
+    const char* rp[NP];
+    u32x4_t reg[NP];
     long long delta;
     int switch_stage;
     int lds_off;
@@ -135,71 +100,121 @@ struct SplitRowLoader {
     __device__ __forceinline__ void init() {
         lds_off = (threadIdx.x >> 3) * kRowBytes + (threadIdx.x & 7) * 16;
     }
+    static __device__ __forceinline__ int row(int p) { return (threadIdx.x >> 3) + p * RPP; }
     __device__ __forceinline__ void gload(int s) {
         const long long off = (s < switch_stage) ? (long long)s * (BK * 2)
                                                  : delta + (long long)(s - switch_stage) * (BK * 2);
 #pragma unroll
-        for (int p = 0; p < NROWS32; ++p) reg[p] = *(const u32x4_t*)(rp[p] + off);
+        for (int p = 0; p < NP; ++p) reg[p] = *(const u32x4_t*)(rp[p] + off);
     }
     __device__ __forceinline__ void sstore(char* base) {
 #pragma unroll
-        for (int p = 0; p < NROWS32; ++p) *(u32x4_t*)(base + lds_off + p * 32 * kRowBytes) = reg[p];
+        for (int p = 0; p < NP; ++p) *(u32x4_t*)(base + lds_off + p * RPP * kRowBytes) = reg[p];
     }
 };
 
-// StridedLoader for a reduction over K memory rows where K is not a multiple
-// of 64 (the rows of one expert): rows at and beyond K are zero-filled.
-// bp = address of (k = 0, first column of chunk nb).
+// Transposing loaders: the operand's k runs along memory rows and its tile
+// rows (the M or N index) are contiguous in memory, e.g. weights [K,N] in the
+// forward pass.  The tile has NCH chunks of 8 consecutive tile rows; thread
+// (kq = tid / NCH, chunk = tid % NCH) fetches KR = 64*NCH/NT consecutive k-rows
+// of its chunk (16 bytes each), transposes the KR x 8 block in registers and
+// writes, for j = 0..7, the KR k-values of tile row chunk*8 + j to LDS row
+// j*NCH + chunk.  Chunks outside the matrix alias a valid chunk.
+template <int KR>
+__device__ __forceinline__ void transpose_store(const u32x4_t (&in)[KR], char* dst, int row_stride) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        uint32_t o[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int p = 0; p < KR / 2; ++p) {
+            const uint32_t lo = in[2 * p][j >> 1], hi = in[2 * p + 1][j >> 1];
+            o[p] = (j & 1) ? ((lo >> 16) | (hi & 0xffff0000u)) : ((lo & 0xffffu) | (hi << 16));
+        }
+        char* d = dst + j * row_stride;
+        if (KR == 8) *(u32x4_t*)d = u32x4_t{o[0], o[1], o[2], o[3]};
+        else if (KR == 4) *(u32x2_t*)d = u32x2_t{o[0], o[1]};
+        else *(uint32_t*)d = o[0];
+    }
+}
+
+template <int NT, int NCH>
+struct TrGeom {
+    static constexpr int KQ = NT / NCH;    // threads along k
+    static constexpr int KR = BK / KQ;     // k-rows per thread
+    static_assert(KR == 8 || KR == 4 || KR == 2, "unsupported transposing loader shape");
+    static __device__ __forceinline__ int chunk() { return threadIdx.x % NCH; }
+    static __device__ __forceinline__ int k0() { return (threadIdx.x / NCH) * KR; }
+    static __device__ __forceinline__ int lds_off() { return chunk() * kRowBytes + k0() * 2; }
+};
+
+// Dense matrix, K a multiple of 64.  bp = address of (k = k0() of stage 0,
+// first element of this thread's chunk).
+template <int NT, int NCH>
+struct StridedLoader {
+    typedef TrGeom<NT, NCH> TG;
+    const char* bp;
+    size_t ld_bytes;
+    u32x4_t reg[TG::KR];
+    int lds_off;
+
+    __device__ __forceinline__ void init() { lds_off = TG::lds_off(); }
+    __device__ __forceinline__ void gload(int s) {
+        const char* p = bp + (size_t)s * BK * ld_bytes;
+#pragma unroll
+        for (int r = 0; r < TG::KR; ++r) reg[r] = *(const u32x4_t*)(p + r * ld_bytes);
+    }
+    __device__ __forceinline__ void sstore(char* base) {
+        transpose_store<TG::KR>(reg, base + lds_off, NCH * kRowBytes);
+    }
+};
+
+// Reduction over K memory rows where K is not a multiple of 64 (the rows of one
+// expert): k-rows at and beyond K are zero-filled.  bp = address of (k = 0,
+// first element of this thread's chunk).
+template <int NT, int NCH>
 struct StridedLoaderK {
+    typedef TrGeom<NT, NCH> TG;
     const char* bp;
     size_t ld_bytes;
     int K;
-    u32x4_t reg[8];
-    int lds_off, kb8;
+    u32x4_t reg[TG::KR];
+    int lds_off, k0;
 
-    __device__ __forceinline__ void init() {
-        lds_off = (threadIdx.x & 31) * kRowBytes + (threadIdx.x >> 5) * 16;
-        kb8 = (threadIdx.x >> 5) * 8;
-    }
+    __device__ __forceinline__ void init() { lds_off = TG::lds_off(); k0 = TG::k0(); }
     __device__ __forceinline__ void gload(int s) {
 #pragma unroll
-        for (int r = 0; r < 8; ++r) {
-            const int k = s * BK + kb8 + r;
+        for (int r = 0; r < TG::KR; ++r) {
+            const int k = s * BK + k0 + r;
             const u32x4_t v = *(const u32x4_t*)(bp + (size_t)min(k, K - 1) * ld_bytes);
             reg[r] = (k < K) ? v : zero4();
         }
     }
     __device__ __forceinline__ void sstore(char* base) {
-        u32x4_t out[8];
-        transpose8x8(reg, out);
-#pragma unroll
-        for (int j = 0; j < 8; ++j) *(u32x4_t*)(base + lds_off + j * 32 * kRowBytes) = out[j];
+        transpose_store<TG::KR>(reg, base + lds_off, NCH * kRowBytes);
     }
 };
 
 // The same with a gather: memory row of reduction index k is row_tok[row0+k]
 // of a [T, ld] matrix (the token that sits in that expert row), optionally
 // scaled by row_w[row0+k] and rounded to bf16 once (dO = gate * dY).
-// src = matrix base + byte offset of the first column of chunk nb.
-template <bool SCALE>
+// src = matrix base + byte offset of the first element of this thread's chunk.
+template <int NT, int NCH, bool SCALE>
 struct GatherStridedLoader {
+    typedef TrGeom<NT, NCH> TG;
     const char* src;
     size_t ld_bytes;
     const int32_t* row_tok;
     const float* row_w;
     int row0, K;
-    u32x4_t reg[8];
-    float sc[8];
-    int lds_off, kb8;
+    u32x4_t reg[TG::KR];
+    float sc[TG::KR];
+    int lds_off, k0;
 
-    __device__ __forceinline__ void init() {
-        lds_off = (threadIdx.x & 31) * kRowBytes + (threadIdx.x >> 5) * 16;
-        kb8 = (threadIdx.x >> 5) * 8;
-    }
+    __device__ __forceinline__ void init() { lds_off = TG::lds_off(); k0 = TG::k0(); }
     __device__ __forceinline__ void gload(int s) {
 #pragma unroll
-        for (int r = 0; r < 8; ++r) {
-            const int k = s * BK + kb8 + r;
+        for (int r = 0; r < TG::KR; ++r) {
+            const int k = s * BK + k0 + r;
             const int row = row0 + min(k, K - 1);
             const int tok = row_tok[row];
             if (SCALE) sc[r] = row_w[row];
@@ -210,40 +225,59 @@ struct GatherStridedLoader {
     __device__ __forceinline__ void sstore(char* base) {
         if (SCALE) {
 #pragma unroll
-            for (int r = 0; r < 8; ++r)
+            for (int r = 0; r < TG::KR; ++r)
 #pragma unroll
                 for (int q = 0; q < 4; ++q)
                     reg[r][q] = pack_bf16x2(bf16_lo(reg[r][q]) * sc[r], bf16_hi(reg[r][q]) * sc[r]);
         }
-        u32x4_t out[8];
-        transpose8x8(reg, out);
-#pragma unroll
-        for (int j = 0; j < 8; ++j) *(u32x4_t*)(base + lds_off + j * 32 * kRowBytes) = out[j];
+        transpose_store<TG::KR>(reg, base + lds_off, NCH * kRowBytes);
     }
 };
 
+// Tile row (0..32*NW) that LDS row rho of an A operand staged by a transposing
+// loader with NCH = 4*NW chunks holds: LDS row j*NCH + chunk <-> chunk*8 + j.
+template <int NW>
+__device__ __forceinline__ int tr_tile_row(int rho) {
+    return (rho % (4 * NW)) * 8 + rho / (4 * NW);
+}
+
 // ---------------------------------------------------------------- main loop
-// acc[i][f] += A-fragment i  x  B-fragment f over nk stages of 64.
-template <int FM, class AL, class BL>
-__device__ __forceinline__ void mma_mainloop(AL& al, BL& bl, int nk, char* smem,
-                                             f32x16_t (&acc)[FM][8]) {
-    typedef Geom<FM> G;
+// acc[f] += A-fragment (this wave's 32 rows) x B-fragment f over nk stages.
+// `active` = false lets a wave whose rows are all outside the tile skip the
+// matrix work while still taking part in the loads and barriers.
+template <int NW, class AL, class BL>
+__device__ __forceinline__ void mma_mainloop(AL& al, BL& bl, int nk, char* smem, bool active,
+                                             f32x16_t (&acc)[8]) {
+    typedef Geom<NW> G;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 #pragma unroll
-    for (int i = 0; i < FM; ++i)
+    for (int f = 0; f < 8; ++f)
 #pragma unroll
-        for (int f = 0; f < 8; ++f)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][f][v] = 0.f;
+        for (int v = 0; v < 16; ++v) acc[f][v] = 0.f;
     if (nk <= 0) return;   // empty reduction (an expert without rows): the tile is all zeros
+    // wave-uniform, so the branch below is a scalar branch
+    const bool active_u = __builtin_amdgcn_readfirstlane((int)active) != 0;
 
     al.gload(0);
     bl.gload(0);
     al.sstore(smem);
     bl.sstore(smem + G::A_BYTES);
     __syncthreads();
-    const int a_off = (wave * FM * 32 + (lane & 31)) * kRowBytes + (lane >> 5) * 16;
+    const int a_off = (wave * 32 + (lane & 31)) * kRowBytes + (lane >> 5) * 16;
     const int b_off = G::A_BYTES + (lane & 31) * kRowBytes + (lane >> 5) * 16;
+    if (!active_u) {
+        // this wave's rows are all outside the tile: feed the pipeline, skip the matrix work
+        for (int s = 0; s + 1 < nk; ++s) {
+            char* nxt = smem + ((s + 1) & 1) * G::STAGE;
+            al.gload(s + 1);
+            bl.gload(s + 1);
+            al.sstore(nxt);
+            bl.sstore(nxt + G::A_BYTES);
+            __syncthreads();
+        }
+        __syncthreads();
+        return;
+    }
     for (int s = 0; s < nk; ++s) {
         char* cur = smem + (s & 1) * G::STAGE;
         char* nxt = smem + ((s + 1) & 1) * G::STAGE;
@@ -252,30 +286,18 @@ __device__ __forceinline__ void mma_mainloop(AL& al, BL& bl, int nk, char* smem,
             al.gload(s + 1);
             bl.gload(s + 1);
         }
-        // fragments of sub-step kk+1 are read while the MFMAs of kk run
-        bf16x8_t a[2][FM], b[2][8];
-#pragma unroll
-        for (int i = 0; i < FM; ++i) a[0][i] = *(const bf16x8_t*)(cur + a_off + i * 32 * kRowBytes);
-#pragma unroll
-        for (int f = 0; f < 8; ++f) b[0][f] = *(const bf16x8_t*)(cur + b_off + f * 32 * kRowBytes);
 #pragma unroll
         for (int kk = 0; kk < BK / 16; ++kk) {
-            const int c = kk & 1, n = c ^ 1;
+            bf16x8_t a, b[8];
             __builtin_amdgcn_sched_barrier(0);
-            if (kk + 1 < BK / 16) {
+            a = *(const bf16x8_t*)(cur + a_off + kk * 32);
 #pragma unroll
-                for (int i = 0; i < FM; ++i)
-                    a[n][i] = *(const bf16x8_t*)(cur + a_off + i * 32 * kRowBytes + (kk + 1) * 32);
-#pragma unroll
-                for (int f = 0; f < 8; ++f)
-                    b[n][f] = *(const bf16x8_t*)(cur + b_off + f * 32 * kRowBytes + (kk + 1) * 32);
-            }
+            for (int f = 0; f < 8; ++f)
+                b[f] = *(const bf16x8_t*)(cur + b_off + f * 32 * kRowBytes + kk * 32);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int i = 0; i < FM; ++i)
-#pragma unroll
-                for (int f = 0; f < 8; ++f)
-                    acc[i][f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[c][i], b[c][f], acc[i][f], 0, 0, 0);
+            for (int f = 0; f < 8; ++f)
+                acc[f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b[f], acc[f], 0, 0, 0);
         }
         if (more) {
             al.sstore(nxt);
@@ -285,12 +307,11 @@ __device__ __forceinline__ void mma_mainloop(AL& al, BL& bl, int nk, char* smem,
     }
 }
 
-// Pack the 8 consecutive columns a lane holds for (fragment row i, element v).
-template <int FM>
-__device__ __forceinline__ u32x4_t pack_row8(const f32x16_t (&acc)[FM][8], int i, int v) {
+// Pack the 8 consecutive columns a lane holds for accumulator element v.
+__device__ __forceinline__ u32x4_t pack_row8(const f32x16_t (&acc)[8], int v) {
     u32x4_t r;
 #pragma unroll
-    for (int q = 0; q < 4; ++q) r[q] = pack_bf16x2(acc[i][2 * q][v], acc[i][2 * q + 1][v]);
+    for (int q = 0; q < 4; ++q) r[q] = pack_bf16x2(acc[2 * q][v], acc[2 * q + 1][v]);
     return r;
 }
 
