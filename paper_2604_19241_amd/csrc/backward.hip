@@ -72,17 +72,31 @@ __global__ void __launch_bounds__(256) row_meta_kernel(BwdParams p) {
     }
 }
 
+// One workgroup: row tiles, per-XCD task lists, cleared scoreboard.  List order
+// per XCD (experts i = 0..n-1 of that list): [dH_0, dWdown_0], [dH_1, dWdown_1],
+// [dXp_0, dWgu_0], [dH_2, dWdown_2], [dXp_1, dWgu_1], ...: the consumers of
+// expert i sit one expert behind its producers.
 template <int BM>
 __global__ void __launch_bounds__(1024) bwd_prologue_kernel(BwdParams p) {
     __shared__ int32_t s_scan[kMaxExperts];
+    __shared__ int32_t s_ga[kMaxExperts];
+    __shared__ int32_t s_gb[kMaxExperts];
+    __shared__ int32_t s_rt0[kMaxExperts];
+    __shared__ int32_t s_ta[kMaxExperts];
+    __shared__ int32_t s_tb[kMaxExperts];
+    __shared__ int32_t s_qbase[kQueues + 1];
+    __shared__ int32_t s_lag;
     const int e = threadIdx.x;
     const int ec = p.s.e_count;
+    const int per_dwd = p.mt_dwd * p.nt_dwd, per_dwgu = p.mt_dwgu * p.nt_dwgu;
     int cnt = 0, nt = 0;
     if (e < ec) {
         cnt = p.offsets[e + 1] - p.offsets[e];
         nt = (cnt + BM - 1) / BM;
     }
     s_scan[e] = nt;
+    s_ga[e] = (e < ec) ? nt * p.nct_dh + per_dwd : 0;
+    s_gb[e] = (e < ec) ? nt * p.nct_dxp + per_dwgu : 0;
     __syncthreads();
     for (int off = 1; off < kMaxExperts; off <<= 1) {
         const int32_t add = (e >= off) ? s_scan[e - off] : 0;
@@ -91,8 +105,20 @@ __global__ void __launch_bounds__(1024) bwd_prologue_kernel(BwdParams p) {
         __syncthreads();
     }
     const int nrt = s_scan[kMaxExperts - 1];
+    if (e == 0) {
+        int base = 0;
+        for (int q = 0; q < kQueues; ++q) {
+            s_qbase[q] = base;
+            for (int j = q; j < ec; j += kQueues) base += s_ga[j] + s_gb[j];
+        }
+        s_qbase[kQueues] = base;
+        int tot = 0;
+        for (int j = 0; j < ec; ++j) tot += s_ga[j];
+        s_lag = queue_lag(tot, ec);
+    }
+    __syncthreads();
     if (e < ec) {
-        const int base = s_scan[e] - nt;
+        const int rt0 = s_scan[e] - nt;
         const int r0 = p.offsets[e];
         for (int i = 0; i < nt; ++i) {
             RowTile t;
@@ -100,42 +126,37 @@ __global__ void __launch_bounds__(1024) bwd_prologue_kernel(BwdParams p) {
             t.row0 = r0 + i * BM;
             t.rows = min(BM, cnt - i * BM);
             t.pad = 0;
-            p.rt[base + i] = t;
+            p.rt[rt0 + i] = t;
+            p.flag_rt[rt0 + i] = 0;
         }
         p.flag_e[e] = 0;
         p.need_e[e] = nt * p.nct_dh;
+        int pa, pb;
+        queue_positions(s_ga, s_gb, e, ec, s_lag, pa, pb);
+        s_rt0[e] = rt0;
+        s_ta[e] = s_qbase[e & (kQueues - 1)] + pa;
+        s_tb[e] = s_qbase[e & (kQueues - 1)] + pb;
     }
-    const int n0 = nrt * p.nct_dh;
-    const int per1 = p.mt_dwd * p.nt_dwd, n1 = ec * per1;
-    const int n2 = nrt * p.nct_dxp;
-    const int per3 = p.mt_dwgu * p.nt_dwgu, n3 = ec * per3;
-    const int n4 = (p.s.T + kDxTokens - 1) / kDxTokens;
-    Task* t = p.tasks;
-    for (int i = e; i < n0; i += 1024) t[i] = Task{i / p.nct_dh, (B_DH << 20) | (i % p.nct_dh)};
-    t += n0;
-    for (int i = e; i < n1; i += 1024) {
-        const int ex = i / per1, r = i % per1;
-        t[i] = Task{ex * p.mt_dwd + r / p.nt_dwd, (B_DWD << 20) | (r % p.nt_dwd)};
+    __syncthreads();
+    for (int x = 0; x < ec; ++x) {
+        const int rt0 = s_rt0[x];
+        const int n_dh = s_ga[x] - per_dwd, n_dxp = s_gb[x] - per_dwgu;
+        Task* ta = p.tasks + s_ta[x];
+        Task* tb = p.tasks + s_tb[x];
+        for (int i = e; i < n_dh; i += 1024) ta[i] = Task{rt0 + i / p.nct_dh, (B_DH << 20) | (i % p.nct_dh)};
+        for (int i = e; i < per_dwd; i += 1024)
+            ta[n_dh + i] = Task{x * p.mt_dwd + i / p.nt_dwd, (B_DWD << 20) | (i % p.nt_dwd)};
+        for (int i = e; i < n_dxp; i += 1024) tb[i] = Task{rt0 + i / p.nct_dxp, (B_DXP << 20) | (i % p.nct_dxp)};
+        for (int i = e; i < per_dwgu; i += 1024)
+            tb[n_dxp + i] = Task{x * p.mt_dwgu + i / p.nt_dwgu, (B_DWGU << 20) | (i % p.nt_dwgu)};
     }
-    t += n1;
-    for (int i = e; i < n2; i += 1024) t[i] = Task{i / p.nct_dxp, (B_DXP << 20) | (i % p.nct_dxp)};
-    t += n2;
-    for (int i = e; i < n3; i += 1024) {
-        const int ex = i / per3, r = i % per3;
-        t[i] = Task{ex * p.mt_dwgu + r / p.nt_dwgu, (B_DWGU << 20) | (r % p.nt_dwgu)};
-    }
-    t += n3;
-    for (int i = e; i < n4; i += 1024) t[i] = Task{i, (B_DX << 20)};
-    for (int i = e; i < nrt; i += 1024) p.flag_rt[i] = 0;
     if (e < CTRL_WORDS) {
-        const int ends[5] = {n0, n0 + n1, n0 + n1 + n2, n0 + n1 + n2 + n3, n0 + n1 + n2 + n3 + n4};
         int v = 0;
         if (e == CTRL_NRT) v = nrt;
-        if (e == CTRL_NTASK) v = ends[4];
-        for (int ph = 0; ph < 5; ++ph) {
-            if (e == CTRL_PHASE_END + ph) v = ends[ph];
-            if (ph > 0 && e == CTRL_CURSOR + 1 + ph) v = ends[ph - 1];
-        }
+        if (e == CTRL_NTAIL) v = (p.s.T + kDxTokens - 1) / kDxTokens;
+        if (e == CTRL_NWAIT) v = nrt * p.nct_dxp;
+        if (e >= CTRL_QLEN && e < CTRL_QLEN + kQueues) v = s_qbase[e - CTRL_QLEN + 1] - s_qbase[e - CTRL_QLEN];
+        if (e >= CTRL_QBASE && e < CTRL_QBASE + kQueues) v = s_qbase[e - CTRL_QBASE];
         p.ctrl[e] = v;
     }
 }
@@ -379,50 +400,55 @@ __device__ __forceinline__ void dx_task(const BwdParams& p, int block) {
 
 // ------------------------------------------------------------- worker loop
 template <int NW>
-__global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW / 4, NW / 4)))
+__global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
 bwd_worker_kernel(BwdParams p, int phase) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     __shared__ int s_task;
     __shared__ int s_ok;
     int* ctrl = p.ctrl;
-    const int end = (phase < 0) ? ctrl[CTRL_NTASK] : ctrl[CTRL_PHASE_END + phase];
-    int* cursor = ctrl + CTRL_CURSOR + (phase < 0 ? 0 : 1 + phase);
-    const int n_dxp = ctrl[CTRL_PHASE_END + 2] - ctrl[CTRL_PHASE_END + 1];
+    const int pass = phase < 0 ? 0 : 1 + phase;
+    const int home = xcc_id();
+    unsigned exhausted = 0;
     for (;;) {
-        if (threadIdx.x == 0) s_task = atomicAdd(cursor, 1);
+        if (threadIdx.x == 0)
+            s_task = fetch_task(ctrl, pass, home, exhausted, phase != B_DX, phase < 0 || phase == B_DX);
         __syncthreads();
         const int id = s_task;
-        if (id >= end) break;
-        const Task task = p.tasks[id];
-        const int type = task.type_ct >> 20, ct = task.type_ct & 0xfffff;
-        if (type == B_DH) {
-            const RowTile rt = p.rt[task.rt];
-            dh_task<NW>(p, rt, ct, smem);
-            __syncthreads();
-            if (threadIdx.x == 0) {
-                add_release(p.flag_rt + task.rt, 1);
-                add_release(p.flag_e + rt.expert, 1);
-            }
-        } else if (type == B_DWD) {
-            dwd_task<NW>(p, task.rt / p.mt_dwd, task.rt % p.mt_dwd, ct, smem);
-        } else if (type == B_DXP) {
-            if (threadIdx.x == 0) s_ok = wait_ge(p.flag_rt + task.rt, p.nct_dh, ctrl, p.spin_ticks);
-            __syncthreads();
-            if (s_ok) {
+        if (id == kFetchDone) break;
+        if (id >= 0) {
+            const Task task = p.tasks[id];
+            const int type = task.type_ct >> 20, ct = task.type_ct & 0xfffff;
+            if (phase >= 0 && type != phase) {
+                // staged launch: another phase's task
+            } else if (type == B_DH) {
                 const RowTile rt = p.rt[task.rt];
-                dxp_task<NW>(p, rt, ct, smem);
+                dh_task<NW>(p, rt, ct, smem);
+                __syncthreads();
+                if (threadIdx.x == 0) {
+                    add_release(p.flag_rt + task.rt, 1);
+                    add_release(p.flag_e + rt.expert, 1);
+                }
+            } else if (type == B_DWD) {
+                dwd_task<NW>(p, task.rt / p.mt_dwd, task.rt % p.mt_dwd, ct, smem);
+            } else if (type == B_DXP) {
+                if (threadIdx.x == 0) s_ok = wait_ge(p.flag_rt + task.rt, p.nct_dh, ctrl, p.spin_ticks);
+                __syncthreads();
+                if (s_ok) {
+                    const RowTile rt = p.rt[task.rt];
+                    dxp_task<NW>(p, rt, ct, smem);
+                }
+                __syncthreads();
+                if (threadIdx.x == 0) add_release(ctrl + CTRL_DONE, 1);
+            } else {
+                const int e = task.rt / p.mt_dwgu;
+                if (threadIdx.x == 0) s_ok = wait_ge(p.flag_e + e, p.need_e[e], ctrl, p.spin_ticks);
+                __syncthreads();
+                if (s_ok) dwgu_task<NW>(p, e, task.rt % p.mt_dwgu, ct, smem);
             }
-            __syncthreads();
-            if (threadIdx.x == 0) add_release(ctrl + CTRL_DONE + 2, 1);
-        } else if (type == B_DWGU) {
-            const int e = task.rt / p.mt_dwgu;
-            if (threadIdx.x == 0) s_ok = wait_ge(p.flag_e + e, p.need_e[e], ctrl, p.spin_ticks);
-            __syncthreads();
-            if (s_ok) dwgu_task<NW>(p, e, task.rt % p.mt_dwgu, ct, smem);
         } else {
-            if (threadIdx.x == 0) s_ok = wait_ge(ctrl + CTRL_DONE + 2, n_dxp, ctrl, p.spin_ticks);
+            if (threadIdx.x == 0) s_ok = wait_ge(ctrl + CTRL_DONE, ctrl[CTRL_NWAIT], ctrl, p.spin_ticks);
             __syncthreads();
-            if (s_ok) dx_task<NW>(p, task.rt);
+            if (s_ok) dx_task<NW>(p, -1 - id);
         }
         __syncthreads();
     }

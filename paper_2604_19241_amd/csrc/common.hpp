@@ -29,7 +29,11 @@ __device__ __forceinline__ float bf16_hi(uint32_t u) { return __uint_as_float(u 
 
 // ---- scoreboard primitives (agent scope: visible across all 8 XCDs' L2s)
 __device__ __forceinline__ int ld_acquire(const int* p) {
+#ifdef UNIEP_NO_ACQUIRE   // timing experiments only
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#else
     return __hip_atomic_load(p, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
+#endif
 }
 __device__ __forceinline__ int ld_relaxed(const int* p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -38,16 +42,96 @@ __device__ __forceinline__ void add_release(int* p, int v) {
     __hip_atomic_fetch_add(p, v, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// ---- work queues -----------------------------------------------------------
+// The GEMM tasks are cut into kQueues lists, one per XCD (each XCD has its own
+// L2): expert e goes to list e % kQueues, so the tiles that share an expert's
+// weights and rows run on one XCD and meet in its L2, and an expert's consumer
+// tiles (GEMM2 / dXp, dW_gate, dW_up) find the producer's output in that L2.
+// Inside a list the experts are pipelined with a lag of one: producer block of
+// expert i+1 comes before the consumer block of expert i, so consumers rarely
+// wait.  A workgroup drains its own XCD's list first and then steals from the
+// others; the token-parallel tail tasks (combine / dX) come last.  Dependencies
+// point to earlier entries of the same list, and an entry is fetched only by a
+// running workgroup, so the lowest unfinished entry of every list can always run.
+constexpr int kQueues = 8;
+constexpr int kPasses = 6;   // cursor sets: 0 = persistent launch, 1+p = staged launch of phase p
+
 // Control words at the head of a forward/backward workspace.
 enum CtrlWord {
     CTRL_STATUS = 0,   // 0 ok, else MOE_ERR_DEVICE
     CTRL_NRT = 1,      // number of row tiles
-    CTRL_NTASK = 2,    // total tasks
-    CTRL_PHASE_END = 4,  // [4..11] exclusive end task id of phase 0..7
-    CTRL_CURSOR = 12,    // [12..20] cursors: [12] whole queue, [13+p] phase p
-    CTRL_DONE = 24,      // [24..31] completion counters per phase
-    CTRL_WORDS = 64
+    CTRL_NTAIL = 2,    // number of tail tasks
+    CTRL_NWAIT = 3,    // completions the tail tasks wait for
+    CTRL_DONE = 4,     // completion counter of the last GEMM phase
+    CTRL_WAIT_TICKS = 5,   // sum over workers of 10 ns ticks spent in scoreboard waits (diagnostic)
+    CTRL_QLEN = 8,     // [8]  entries per list
+    CTRL_QBASE = 16,   // [8]  first entry of each list in the task array
+    CTRL_CURSOR = 24,  // [kPasses][kQueues + 1]  list cursors and tail cursor per pass
+    CTRL_WORDS = 24 + kPasses * (kQueues + 1) + 2
 };
+
+constexpr int kFetchDone = INT32_MIN;
+
+__device__ __forceinline__ int xcc_id() {
+    unsigned v;
+    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(v));
+    return (int)(v & (kQueues - 1));
+}
+
+// Called by one thread.  Returns an index into the task array (>= 0), or
+// -1 - t for tail task t, or kFetchDone.  `exhausted` is the caller's bitmask of
+// lists already seen empty.  use_lists / use_tail restrict a staged launch.
+__device__ __forceinline__ int fetch_task(int* ctrl, int pass, int home, unsigned& exhausted,
+                                          bool use_lists, bool use_tail) {
+    int* cur = ctrl + CTRL_CURSOR + pass * (kQueues + 1);
+    if (use_lists) {
+        for (int i = 0; i < kQueues; ++i) {
+            const int q = (home + i) & (kQueues - 1);
+            if (exhausted & (1u << q)) continue;
+            const int len = ctrl[CTRL_QLEN + q];
+            const int id = (len > 0) ? atomicAdd(cur + q, 1) : len;
+            if (id < len) return ctrl[CTRL_QBASE + q] + id;
+            exhausted |= 1u << q;
+        }
+    }
+    if (use_tail) {
+        const int t = atomicAdd(cur + kQueues, 1);
+        if (t < ctrl[CTRL_NTAIL]) return -1 - t;
+    }
+    return kFetchDone;
+}
+
+// Position of expert e's producer block (pos_a) and consumer block (pos_b)
+// inside its list, given the block sizes ga[], gb[] of all experts (shared
+// memory) and the lag L >= 1: the consumer block of expert i follows the
+// producer block of expert i+L.  List order for L = 1:
+// A0, A1, B0, A2, B1, ..., A(n-1), B(n-2), B(n-1).
+__device__ __forceinline__ void queue_positions(const int* ga, const int* gb, int e, int ec, int lag,
+                                                int& pos_a, int& pos_b) {
+    const int q = e & (kQueues - 1), i = e / kQueues;
+    const int nq = (ec - q + kQueues - 1) / kQueues;
+    int sa_i = 0, sb_i = 0, sb_lag = 0, sa_n = 0;
+    const int lim = min(i + lag + 1, nq);
+    for (int j = 0; j < lim; ++j) {
+        const int ej = q + kQueues * j;
+        if (j < i) {
+            sa_i += ga[ej];
+            sb_i += gb[ej];
+            if (j < i - lag) sb_lag += gb[ej];
+        }
+        sa_n += ga[ej];
+    }
+    pos_a = sa_i + sb_lag;
+    pos_b = sa_n + sb_i;
+}
+
+// Lag (in experts) between an expert's producer and consumer blocks: enough
+// producer tasks in between that a workgroup which runs ahead finds other
+// producers to do instead of waiting (about 1.5 x the workgroups of one XCD).
+__device__ __forceinline__ int queue_lag(int total_producer_tasks, int ec) {
+    const int per = max(1, total_producer_tasks / max(1, ec));
+    return min(8, max(1, (48 + per - 1) / per));
+}
 
 // Bounded wait for *p >= need.  Returns false (and raises the status word) if
 // the bound is exceeded or another worker already raised it, so that every
@@ -57,7 +141,10 @@ __device__ __forceinline__ bool wait_ge(const int* p, int need, int* ctrl, long 
     const long long t0 = wall_clock64();
     for (;;) {
         __builtin_amdgcn_s_sleep(8);
-        if (ld_acquire(p) >= need) return true;
+        if (ld_acquire(p) >= need) {
+            atomicAdd(ctrl + CTRL_WAIT_TICKS, (int)(wall_clock64() - t0));
+            return true;
+        }
         if (ld_relaxed(ctrl + CTRL_STATUS) != 0) return false;
         if (wall_clock64() - t0 > limit_ticks) {
             __hip_atomic_store(ctrl + CTRL_STATUS, (int)MOE_ERR_DEVICE, __ATOMIC_RELAXED,

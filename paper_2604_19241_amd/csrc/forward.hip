@@ -41,12 +41,16 @@ struct FwdParams {
 };
 
 // ------------------------------------------------------------- prologue
-// One workgroup: row-tile table from the expert offsets, the linearised task
-// list (producers before consumers, experts ascending inside each phase), and
-// a cleared scoreboard.
+// One workgroup: row-tile table from the expert offsets, the per-XCD task lists
+// (GEMM1 block of expert i+1 ahead of the GEMM2 block of expert i) and a
+// cleared scoreboard.
 template <int BM>
 __global__ void __launch_bounds__(1024) fwd_prologue_kernel(FwdParams p) {
     __shared__ int32_t s_scan[kMaxExperts];
+    __shared__ int32_t s_g1[kMaxExperts];
+    __shared__ int32_t s_g2[kMaxExperts];
+    __shared__ int32_t s_qbase[kQueues + 1];
+    __shared__ int32_t s_lag;
     const int e = threadIdx.x;
     const int ec = p.s.e_count;
     int cnt = 0, nt = 0;
@@ -55,6 +59,8 @@ __global__ void __launch_bounds__(1024) fwd_prologue_kernel(FwdParams p) {
         nt = (cnt + BM - 1) / BM;
     }
     s_scan[e] = nt;
+    s_g1[e] = nt * p.nct1;
+    s_g2[e] = nt * p.nct2;
     __syncthreads();
     for (int off = 1; off < kMaxExperts; off <<= 1) {
         const int32_t add = (e >= off) ? s_scan[e - off] : 0;
@@ -63,8 +69,23 @@ __global__ void __launch_bounds__(1024) fwd_prologue_kernel(FwdParams p) {
         __syncthreads();
     }
     const int nrt = s_scan[kMaxExperts - 1];
+    if (e == 0) {
+        int base = 0;
+        for (int q = 0; q < kQueues; ++q) {
+            s_qbase[q] = base;
+            for (int j = q; j < ec; j += kQueues) base += s_g1[j] + s_g2[j];
+        }
+        s_qbase[kQueues] = base;
+        int tot = 0;
+        for (int j = 0; j < ec; ++j) tot += s_g1[j];
+        s_lag = queue_lag(tot, ec);
+    }
+    __syncthreads();
+    __shared__ int32_t s_rt0[kMaxExperts];
+    __shared__ int32_t s_t1[kMaxExperts];
+    __shared__ int32_t s_t2[kMaxExperts];
     if (e < ec) {
-        const int base = s_scan[e] - nt;
+        const int rt0 = s_scan[e] - nt;
         const int r0 = p.offsets[e];
         for (int i = 0; i < nt; ++i) {
             RowTile t;
@@ -72,25 +93,30 @@ __global__ void __launch_bounds__(1024) fwd_prologue_kernel(FwdParams p) {
             t.row0 = r0 + i * BM;
             t.rows = min(BM, cnt - i * BM);
             t.pad = 0;
-            p.rt[base + i] = t;
+            p.rt[rt0 + i] = t;
+            p.flag1[rt0 + i] = 0;
         }
+        int pos1, pos2;
+        queue_positions(s_g1, s_g2, e, ec, s_lag, pos1, pos2);
+        s_rt0[e] = rt0;
+        s_t1[e] = s_qbase[e & (kQueues - 1)] + pos1;
+        s_t2[e] = s_qbase[e & (kQueues - 1)] + pos2;
     }
-    const int n1 = nrt * p.nct1, n2 = nrt * p.nct2;
-    const int n3 = (p.s.T + kCombineTokens - 1) / kCombineTokens;
-    for (int i = e; i < n1; i += 1024) p.tasks[i] = Task{i / p.nct1, (TASK_GEMM1 << 20) | (i % p.nct1)};
-    for (int i = e; i < n2; i += 1024)
-        p.tasks[n1 + i] = Task{i / p.nct2, (TASK_GEMM2 << 20) | (i % p.nct2)};
-    for (int i = e; i < n3; i += 1024) p.tasks[n1 + n2 + i] = Task{i, (TASK_COMBINE << 20)};
-    for (int i = e; i < nrt; i += 1024) p.flag1[i] = 0;
+    __syncthreads();
+    for (int x = 0; x < ec; ++x) {   // all threads write each expert's two blocks
+        const int rt0 = s_rt0[x];
+        Task* t1 = p.tasks + s_t1[x];
+        Task* t2 = p.tasks + s_t2[x];
+        for (int i = e; i < s_g1[x]; i += 1024) t1[i] = Task{rt0 + i / p.nct1, (TASK_GEMM1 << 20) | (i % p.nct1)};
+        for (int i = e; i < s_g2[x]; i += 1024) t2[i] = Task{rt0 + i / p.nct2, (TASK_GEMM2 << 20) | (i % p.nct2)};
+    }
     if (e < CTRL_WORDS) {
         int v = 0;
         if (e == CTRL_NRT) v = nrt;
-        if (e == CTRL_NTASK) v = n1 + n2 + n3;
-        if (e == CTRL_PHASE_END + 0) v = n1;
-        if (e == CTRL_PHASE_END + 1) v = n1 + n2;
-        if (e == CTRL_PHASE_END + 2) v = n1 + n2 + n3;
-        if (e == CTRL_CURSOR + 1 + 1) v = n1;        // phase cursors start at their phase
-        if (e == CTRL_CURSOR + 1 + 2) v = n1 + n2;
+        if (e == CTRL_NTAIL) v = (p.s.T + kCombineTokens - 1) / kCombineTokens;
+        if (e == CTRL_NWAIT) v = nrt * p.nct2;
+        if (e >= CTRL_QLEN && e < CTRL_QLEN + kQueues) v = s_qbase[e - CTRL_QLEN + 1] - s_qbase[e - CTRL_QLEN];
+        if (e >= CTRL_QBASE && e < CTRL_QBASE + kQueues) v = s_qbase[e - CTRL_QBASE];
         p.ctrl[e] = v;
     }
 }
@@ -241,44 +267,50 @@ __device__ __forceinline__ void combine_task(const FwdParams& p, int block) {
 }
 
 // ------------------------------------------------------------- the worker loop
-// phase < 0: the whole queue with scoreboard waits (persistent MegaKernel).
+// phase < 0: all tasks with scoreboard waits (persistent MegaKernel).
 // phase >= 0: only that phase's tasks (staged schedule; the waits are already
 // satisfied by stream order).
 template <int NW>
-__global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW / 4, NW / 4)))
+__global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
 fwd_worker_kernel(FwdParams p, int phase) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     __shared__ int s_task;
     __shared__ int s_ok;
     int* ctrl = p.ctrl;
-    const int end = (phase < 0) ? ctrl[CTRL_NTASK] : ctrl[CTRL_PHASE_END + phase];
-    int* cursor = ctrl + CTRL_CURSOR + (phase < 0 ? 0 : 1 + phase);
-    const int n2_total = ctrl[CTRL_PHASE_END + 1] - ctrl[CTRL_PHASE_END + 0];
+    const int pass = phase < 0 ? 0 : 1 + phase;
+    const int home = xcc_id();
+    unsigned exhausted = 0;
     for (;;) {
-        if (threadIdx.x == 0) s_task = atomicAdd(cursor, 1);
+        if (threadIdx.x == 0)
+            s_task = fetch_task(ctrl, pass, home, exhausted, phase != TASK_COMBINE,
+                                phase < 0 || phase == TASK_COMBINE);
         __syncthreads();
         const int id = s_task;
-        if (id >= end) break;
-        const Task task = p.tasks[id];
-        const int type = task.type_ct >> 20, ct = task.type_ct & 0xfffff;
-        if (type == TASK_GEMM1) {
-            const RowTile rt = p.rt[task.rt];
-            gemm1_task<NW>(p, rt, ct, smem);
-            __syncthreads();   // all h stores of the tile issued and complete at workgroup scope
-            if (threadIdx.x == 0) add_release(p.flag1 + task.rt, 1);
-        } else if (type == TASK_GEMM2) {
-            if (threadIdx.x == 0) s_ok = wait_ge(p.flag1 + task.rt, p.nct1, ctrl, p.spin_ticks);
-            __syncthreads();
-            if (s_ok) {
+        if (id == kFetchDone) break;
+        if (id >= 0) {
+            const Task task = p.tasks[id];
+            const int type = task.type_ct >> 20, ct = task.type_ct & 0xfffff;
+            if (phase >= 0 && type != phase) {
+                // staged launch: another phase's task, nothing to do
+            } else if (type == TASK_GEMM1) {
                 const RowTile rt = p.rt[task.rt];
-                gemm2_task<NW>(p, rt, ct, smem);
+                gemm1_task<NW>(p, rt, ct, smem);
+                __syncthreads();   // all h stores of the tile are complete at workgroup scope
+                if (threadIdx.x == 0) add_release(p.flag1 + task.rt, 1);
+            } else {
+                if (threadIdx.x == 0) s_ok = wait_ge(p.flag1 + task.rt, p.nct1, ctrl, p.spin_ticks);
+                __syncthreads();
+                if (s_ok) {
+                    const RowTile rt = p.rt[task.rt];
+                    gemm2_task<NW>(p, rt, ct, smem);
+                }
+                __syncthreads();
+                if (threadIdx.x == 0) add_release(ctrl + CTRL_DONE, 1);
             }
-            __syncthreads();
-            if (threadIdx.x == 0) add_release(ctrl + CTRL_DONE + 1, 1);
         } else {
-            if (threadIdx.x == 0) s_ok = wait_ge(ctrl + CTRL_DONE + 1, n2_total, ctrl, p.spin_ticks);
+            if (threadIdx.x == 0) s_ok = wait_ge(ctrl + CTRL_DONE, ctrl[CTRL_NWAIT], ctrl, p.spin_ticks);
             __syncthreads();
-            if (s_ok) combine_task<NW>(p, task.rt);
+            if (s_ok) combine_task<NW>(p, -1 - id);
         }
         __syncthreads();   // s_task / s_ok are rewritten next round
     }
@@ -385,5 +417,6 @@ int fwd_launch(const moe_shape_t& s, const void* x, const void* w_gate, const vo
     p.spin_ticks = (long long)ms * 100000ll;   // wall_clock64 ticks at 100 MHz
     return nw == 4 ? fwd_launch_nw<4>(p, opts, st) : fwd_launch_nw<8>(p, opts, st);
 }
+
 
 }  // namespace uniep

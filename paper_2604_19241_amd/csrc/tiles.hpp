@@ -21,6 +21,14 @@
 
 namespace uniep {
 
+// Timing experiments only: -DUNIEP_ALIAS_STAGE0 makes every K-stage re-read stage 0
+// (tiny memory footprint, wrong results) to separate memory stalls from issue limits.
+#ifdef UNIEP_ALIAS_STAGE0
+#define UNIEP_STAGE_OF(s) 0
+#else
+#define UNIEP_STAGE_OF(s) (s)
+#endif
+
 constexpr int BK = 64;
 constexpr int BN = 256;
 constexpr int kRowBytes = (BK + 8) * 2;   // 144
@@ -32,7 +40,11 @@ struct Geom {
     static constexpr int A_BYTES = BM * kRowBytes;
     static constexpr int B_BYTES = BN * kRowBytes;
     static constexpr int STAGE = A_BYTES + B_BYTES;
-    static constexpr int SMEM = 2 * STAGE;
+    // NW = 8: one workgroup per CU with two LDS stages.  NW = 4: one LDS stage (55 KB) so that
+    // two workgroups share a CU and each hides the other's barriers, prologue and epilogue.
+    static constexpr int NSTAGE = (NW == 8) ? 2 : 1;
+    static constexpr int SMEM = NSTAGE * STAGE;
+    static constexpr int WAVES_PER_SIMD = 2;
 };
 
 // Row inside a 32-row fragment that accumulator element v of this lane holds.
@@ -66,13 +78,16 @@ struct RowLoader {
     }
     // LDS row that pass p of this thread fills
     static __device__ __forceinline__ int row(int p) { return (threadIdx.x >> 3) + p * RPP; }
-    __device__ __forceinline__ void gload(int s) {
+    static constexpr int PP = NP / 4;          // passes per quarter-stage part
+    static_assert(NP % 4 == 0, "row loader needs a multiple of 4 passes");
+    __device__ __forceinline__ void gload_part(int s, int part) {
 #pragma unroll
-        for (int p = 0; p < NP; ++p) reg[p] = *(const u32x4_t*)(rp[p] + (size_t)s * (BK * 2));
+        for (int p = part * PP; p < (part + 1) * PP; ++p)
+            reg[p] = *(const u32x4_t*)(rp[p] + (size_t)UNIEP_STAGE_OF(s) * (BK * 2));
     }
-    __device__ __forceinline__ void sstore(char* base) {
+    __device__ __forceinline__ void sstore_part(char* base, int part) {
 #pragma unroll
-        for (int p = 0; p < NP; ++p) {
+        for (int p = part * PP; p < (part + 1) * PP; ++p) {
             u32x4_t r = reg[p];
             if (SCALE) {
                 const float f = sc[p];
@@ -101,15 +116,18 @@ struct SplitRowLoader {
         lds_off = (threadIdx.x >> 3) * kRowBytes + (threadIdx.x & 7) * 16;
     }
     static __device__ __forceinline__ int row(int p) { return (threadIdx.x >> 3) + p * RPP; }
-    __device__ __forceinline__ void gload(int s) {
+    static constexpr int PP = NP / 4;
+    static_assert(NP % 4 == 0, "row loader needs a multiple of 4 passes");
+    __device__ __forceinline__ void gload_part(int s, int part) {
         const long long off = (s < switch_stage) ? (long long)s * (BK * 2)
                                                  : delta + (long long)(s - switch_stage) * (BK * 2);
 #pragma unroll
-        for (int p = 0; p < NP; ++p) reg[p] = *(const u32x4_t*)(rp[p] + off);
+        for (int p = part * PP; p < (part + 1) * PP; ++p) reg[p] = *(const u32x4_t*)(rp[p] + off);
     }
-    __device__ __forceinline__ void sstore(char* base) {
+    __device__ __forceinline__ void sstore_part(char* base, int part) {
 #pragma unroll
-        for (int p = 0; p < NP; ++p) *(u32x4_t*)(base + lds_off + p * RPP * kRowBytes) = reg[p];
+        for (int p = part * PP; p < (part + 1) * PP; ++p)
+            *(u32x4_t*)(base + lds_off + p * RPP * kRowBytes) = reg[p];
     }
 };
 
@@ -158,12 +176,15 @@ struct StridedLoader {
     int lds_off;
 
     __device__ __forceinline__ void init() { lds_off = TG::lds_off(); }
-    __device__ __forceinline__ void gload(int s) {
-        const char* p = bp + (size_t)s * BK * ld_bytes;
+    // the transpose needs all k-rows of the block: the whole stage moves in part 0
+    __device__ __forceinline__ void gload_part(int s, int part) {
+        if (part != 0) return;
+        const char* p = bp + (size_t)UNIEP_STAGE_OF(s) * BK * ld_bytes;
 #pragma unroll
         for (int r = 0; r < TG::KR; ++r) reg[r] = *(const u32x4_t*)(p + r * ld_bytes);
     }
-    __device__ __forceinline__ void sstore(char* base) {
+    __device__ __forceinline__ void sstore_part(char* base, int part) {
+        if (part != 0) return;
         transpose_store<TG::KR>(reg, base + lds_off, NCH * kRowBytes);
     }
 };
@@ -181,7 +202,8 @@ struct StridedLoaderK {
     int lds_off, k0;
 
     __device__ __forceinline__ void init() { lds_off = TG::lds_off(); k0 = TG::k0(); }
-    __device__ __forceinline__ void gload(int s) {
+    __device__ __forceinline__ void gload_part(int s, int part) {
+        if (part != 0) return;
 #pragma unroll
         for (int r = 0; r < TG::KR; ++r) {
             const int k = s * BK + k0 + r;
@@ -189,7 +211,8 @@ struct StridedLoaderK {
             reg[r] = (k < K) ? v : zero4();
         }
     }
-    __device__ __forceinline__ void sstore(char* base) {
+    __device__ __forceinline__ void sstore_part(char* base, int part) {
+        if (part != 0) return;
         transpose_store<TG::KR>(reg, base + lds_off, NCH * kRowBytes);
     }
 };
@@ -211,7 +234,8 @@ struct GatherStridedLoader {
     int lds_off, k0;
 
     __device__ __forceinline__ void init() { lds_off = TG::lds_off(); k0 = TG::k0(); }
-    __device__ __forceinline__ void gload(int s) {
+    __device__ __forceinline__ void gload_part(int s, int part) {
+        if (part != 0) return;
 #pragma unroll
         for (int r = 0; r < TG::KR; ++r) {
             const int k = s * BK + k0 + r;
@@ -222,7 +246,8 @@ struct GatherStridedLoader {
             reg[r] = (k < K) ? v : zero4();
         }
     }
-    __device__ __forceinline__ void sstore(char* base) {
+    __device__ __forceinline__ void sstore_part(char* base, int part) {
+        if (part != 0) return;
         if (SCALE) {
 #pragma unroll
             for (int r = 0; r < TG::KR; ++r)
@@ -243,6 +268,14 @@ __device__ __forceinline__ int tr_tile_row(int rho) {
 
 // ---------------------------------------------------------------- main loop
 // acc[f] += A-fragment (this wave's 32 rows) x B-fragment f over nk stages.
+//
+// Pipeline: while stage t is multiplied out of LDS buffer t%2, the registers
+// that hold stage t+1 (fetched during stage t-1) are written to the other
+// buffer and immediately refilled with stage t+2.  Both happen in quarter-stage
+// parts between the four k-sub-steps, so global loads are issued continuously
+// and every load has a whole stage of matrix work to arrive.  One barrier per
+// stage.  Stage indices past the end are clamped (a harmless re-read; the
+// extra LDS image is never consumed).
 // `active` = false lets a wave whose rows are all outside the tile skip the
 // matrix work while still taking part in the loads and barriers.
 template <int NW, class AL, class BL>
@@ -258,38 +291,101 @@ __device__ __forceinline__ void mma_mainloop(AL& al, BL& bl, int nk, char* smem,
     // wave-uniform, so the branch below is a scalar branch
     const bool active_u = __builtin_amdgcn_readfirstlane((int)active) != 0;
 
-    al.gload(0);
-    bl.gload(0);
-    al.sstore(smem);
-    bl.sstore(smem + G::A_BYTES);
+#pragma unroll
+    for (int part = 0; part < 4; ++part) {
+        al.gload_part(0, part);
+        bl.gload_part(0, part);
+    }
+#pragma unroll
+    for (int part = 0; part < 4; ++part) {
+        al.sstore_part(smem, part);
+        bl.sstore_part(smem + G::A_BYTES, part);
+    }
+    const int s1 = min(1, nk - 1);
+#pragma unroll
+    for (int part = 0; part < 4; ++part) {
+        al.gload_part(s1, part);
+        bl.gload_part(s1, part);
+    }
     __syncthreads();
     const int a_off = (wave * 32 + (lane & 31)) * kRowBytes + (lane >> 5) * 16;
     const int b_off = G::A_BYTES + (lane & 31) * kRowBytes + (lane >> 5) * 16;
-    if (!active_u) {
-        // this wave's rows are all outside the tile: feed the pipeline, skip the matrix work
-        for (int s = 0; s + 1 < nk; ++s) {
-            char* nxt = smem + ((s + 1) & 1) * G::STAGE;
-            al.gload(s + 1);
-            bl.gload(s + 1);
-            al.sstore(nxt);
-            bl.sstore(nxt + G::A_BYTES);
+    if (G::NSTAGE == 1) {
+        // single LDS stage: multiply, barrier, refill from the prefetch registers, barrier
+        if (!active_u) {
+            for (int t = 0; t + 1 < nk; ++t) {
+                __syncthreads();
+                const int s2 = min(t + 2, nk - 1);
+#pragma unroll
+                for (int part = 0; part < 4; ++part) {
+                    al.sstore_part(smem, part);
+                    bl.sstore_part(smem + G::A_BYTES, part);
+                    al.gload_part(s2, part);
+                    bl.gload_part(s2, part);
+                }
+                __syncthreads();
+            }
             __syncthreads();
+            return;
         }
-        __syncthreads();
+        for (int t = 0; t < nk; ++t) {
+#pragma unroll
+            for (int kk = 0; kk < BK / 16; ++kk) {
+                __builtin_amdgcn_sched_barrier(0);
+                bf16x8_t a, b[8];
+                a = *(const bf16x8_t*)(smem + a_off + kk * 32);
+#pragma unroll
+                for (int f = 0; f < 8; ++f)
+                    b[f] = *(const bf16x8_t*)(smem + b_off + f * 32 * kRowBytes + kk * 32);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int f = 0; f < 8; ++f)
+                    acc[f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b[f], acc[f], 0, 0, 0);
+            }
+            if (t + 1 < nk) {
+                __syncthreads();
+                const int s2 = min(t + 2, nk - 1);
+#pragma unroll
+                for (int part = 0; part < 4; ++part) {
+                    al.sstore_part(smem, part);
+                    bl.sstore_part(smem + G::A_BYTES, part);
+                    al.gload_part(s2, part);
+                    bl.gload_part(s2, part);
+                }
+                __syncthreads();
+            }
+        }
+        __syncthreads();   // the tile's epilogue may not overtake slower waves' last reads
         return;
     }
-    for (int s = 0; s < nk; ++s) {
-        char* cur = smem + (s & 1) * G::STAGE;
-        char* nxt = smem + ((s + 1) & 1) * G::STAGE;
-        const bool more = (s + 1 < nk);
-        if (more) {
-            al.gload(s + 1);
-            bl.gload(s + 1);
+    if (!active_u) {
+        for (int t = 0; t < nk; ++t) {
+            char* nxt = smem + ((t + 1) & 1) * G::STAGE;
+            const int s2 = min(t + 2, nk - 1);
+#pragma unroll
+            for (int part = 0; part < 4; ++part) {
+                al.sstore_part(nxt, part);
+                bl.sstore_part(nxt + G::A_BYTES, part);
+                al.gload_part(s2, part);
+                bl.gload_part(s2, part);
+            }
+            __syncthreads();
         }
+        return;
+    }
+    for (int t = 0; t < nk; ++t) {
+        char* cur = smem + (t & 1) * G::STAGE;
+        char* nxt = smem + ((t + 1) & 1) * G::STAGE;
+        const int s2 = min(t + 2, nk - 1);
 #pragma unroll
         for (int kk = 0; kk < BK / 16; ++kk) {
-            bf16x8_t a, b[8];
             __builtin_amdgcn_sched_barrier(0);
+            al.sstore_part(nxt, kk);
+            bl.sstore_part(nxt + G::A_BYTES, kk);
+            al.gload_part(s2, kk);
+            bl.gload_part(s2, kk);
+            __builtin_amdgcn_sched_barrier(0);
+            bf16x8_t a, b[8];
             a = *(const bf16x8_t*)(cur + a_off + kk * 32);
 #pragma unroll
             for (int f = 0; f < 8; ++f)
@@ -298,10 +394,6 @@ __device__ __forceinline__ void mma_mainloop(AL& al, BL& bl, int nk, char* smem,
 #pragma unroll
             for (int f = 0; f < 8; ++f)
                 acc[f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b[f], acc[f], 0, 0, 0);
-        }
-        if (more) {
-            al.sstore(nxt);
-            bl.sstore(nxt + G::A_BYTES);
         }
         __syncthreads();
     }
