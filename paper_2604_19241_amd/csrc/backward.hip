@@ -168,14 +168,11 @@ __device__ __forceinline__ void dh_task(const BwdParams& p, const RowTile rt, in
     const int d = p.s.d, I = p.s.I;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int kc = tid & 7;
-    typedef RowLoader<G::NT, G::BM, true> AL;
-    AL al;
-    al.init();
-#pragma unroll
-    for (int q = 0; q < AL::NP; ++q) {
-        const int row = rt.row0 + min(AL::row(q), rt.rows - 1);
-        al.rp[q] = p.dy + ((size_t)p.row_tok[row] * d + kc * 8) * 2;
-        al.sc[q] = p.row_w[row];
+    DirectRowLoader<true> al;   // dO = gate * dY, gathered and scaled on the fly
+    {
+        const int row = rt.row0 + min(wave * 32 + (lane & 31), rt.rows - 1);
+        al.rp = p.dy + ((size_t)p.row_tok[row] * d + (lane >> 5) * 32) * 2;
+        al.sc = p.row_w[row];
     }
     typedef RowLoader<G::NT, BN, false> BL;   // B rows are rows of W_down[e]: k (= d) contiguous
     BL bl;
@@ -188,7 +185,7 @@ __device__ __forceinline__ void dh_task(const BwdParams& p, const RowTile rt, in
         bl.rp[q] = p.w_down + (((size_t)rt.expert * I + c) * d + kc * 8) * 2;
     }
     f32x16_t acc[8];
-    mma_mainloop<NW>(al, bl, d / BK, smem, wave * 32 < rt.rows, acc);
+    mma_mainloop_direct<NW>(al, bl, d / BK, smem, wave * 32 < rt.rows, acc);
     // epilogue: SwiGLU backward with the saved G, U of the same rows and columns
     const int col = n0 + (lane & 31) * 8;
     if (col < I) {
@@ -229,13 +226,10 @@ __device__ __forceinline__ void dxp_task(const BwdParams& p, const RowTile rt, i
     const int d = p.s.d, I = p.s.I;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int kc = tid & 7;
-    typedef RowLoader<G::NT, G::BM, false> AL;
-    AL al;
-    al.init();
-#pragma unroll
-    for (int q = 0; q < AL::NP; ++q) {
-        const int row = rt.row0 + min(AL::row(q), rt.rows - 1);
-        al.rp[q] = p.dgu + ((size_t)row * 2 * I + kc * 8) * 2;
+    DirectRowLoader<false> al;
+    {
+        const int row = rt.row0 + min(wave * 32 + (lane & 31), rt.rows - 1);
+        al.rp = p.dgu + ((size_t)row * 2 * I + (lane >> 5) * 32) * 2;
     }
     typedef SplitRowLoader<G::NT, BN> BL;   // k < I: row of W_gate[e][c], k >= I: row of W_up[e][c]
     BL bl;
@@ -250,7 +244,7 @@ __device__ __forceinline__ void dxp_task(const BwdParams& p, const RowTile rt, i
     bl.delta = (long long)(p.w_up - p.w_gate);
     bl.switch_stage = I / BK;
     f32x16_t acc[8];
-    mma_mainloop<NW>(al, bl, 2 * I / BK, smem, wave * 32 < rt.rows, acc);
+    mma_mainloop_direct<NW>(al, bl, 2 * I / BK, smem, wave * 32 < rt.rows, acc);
     const int col = n0 + (lane & 31) * 8;
     if (col < d) {
 #pragma unroll

@@ -15,6 +15,15 @@
 namespace uniep {
 
 enum TaskType { TASK_GEMM1 = 0, TASK_GEMM2 = 1, TASK_COMBINE = 2 };
+
+#ifdef UNIEP_PROFILE   // timing experiments only: 10 ns ticks per task type {fetch, wait, main, epilogue, count}
+__device__ unsigned long long g_prof[3][8];
+#define PROF_NOW() wall_clock64()
+#define PROF_ADD(type, slot, val) do { if (threadIdx.x == 0) atomicAdd(&g_prof[type][slot], (unsigned long long)(val)); } while (0)
+#else
+#define PROF_NOW() 0ll
+#define PROF_ADD(type, slot, val) do { } while (0)
+#endif
 constexpr int kCombineTokens = 16;   // tokens per combine task (4 per wave)
 
 struct FwdParams {
@@ -128,20 +137,15 @@ __global__ void __launch_bounds__(1024) fwd_prologue_kernel(FwdParams p) {
 template <int NW>
 __device__ __forceinline__ void gemm1_task(const FwdParams& p, const RowTile rt, int ct,
                                            char* smem) {
+    const long long t_start = PROF_NOW();
     typedef Geom<NW> G;
     const int d = p.s.d, I = p.s.I, k = p.s.k;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    typedef RowLoader<G::NT, G::BM, false> AL;
-    AL al;
-    al.init();
+    DirectRowLoader<false> al;   // dispatch = gather: each lane reads its token's row of x
     {
-        const int kc = tid & 7;
-#pragma unroll
-        for (int q = 0; q < AL::NP; ++q) {
-            const int m = min(AL::row(q), rt.rows - 1);   // rows past the tile alias its last row
-            const int tok = p.perm[rt.row0 + m] / k;
-            al.rp[q] = p.x + ((size_t)tok * d + kc * 8) * 2;
-        }
+        const int m = min(wave * 32 + (lane & 31), rt.rows - 1);   // rows past the tile alias its last row
+        const int tok = p.perm[rt.row0 + m] / k;
+        al.rp = p.x + ((size_t)tok * d + (lane >> 5) * 32) * 2;
     }
     typedef StridedLoader<G::NT, 32> BL;
     BL bl;
@@ -155,7 +159,9 @@ __device__ __forceinline__ void gemm1_task(const FwdParams& p, const RowTile rt,
         bl.bp = w + (((size_t)rt.expert * d + BL::TG::k0()) * I + hc) * 2;
     }
     f32x16_t acc[8];
-    mma_mainloop<NW>(al, bl, d / BK, smem, wave * 32 < rt.rows, acc);
+    mma_mainloop_direct<NW>(al, bl, d / BK, smem, wave * 32 < rt.rows, acc);
+    PROF_ADD(TASK_GEMM1, 2, PROF_NOW() - t_start);
+    PROF_ADD(TASK_GEMM1, 5, d / BK);
 
     // epilogue: SwiGLU on the accumulators; lanes (2q, 2q+1) trade halves so that
     // each ends with G and U of 4 consecutive h-columns.
@@ -190,19 +196,14 @@ __device__ __forceinline__ void gemm1_task(const FwdParams& p, const RowTile rt,
 template <int NW>
 __device__ __forceinline__ void gemm2_task(const FwdParams& p, const RowTile rt, int ct,
                                            char* smem) {
+    const long long t_start = PROF_NOW();
     typedef Geom<NW> G;
     const int d = p.s.d, I = p.s.I;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    typedef RowLoader<G::NT, G::BM, false> AL;
-    AL al;
-    al.init();
+    DirectRowLoader<false> al;
     {
-        const int kc = tid & 7;
-#pragma unroll
-        for (int q = 0; q < AL::NP; ++q) {
-            const int m = min(AL::row(q), rt.rows - 1);
-            al.rp[q] = p.h + ((size_t)(rt.row0 + m) * I + kc * 8) * 2;
-        }
+        const int m = min(wave * 32 + (lane & 31), rt.rows - 1);
+        al.rp = p.h + ((size_t)(rt.row0 + m) * I + (lane >> 5) * 32) * 2;
     }
     typedef StridedLoader<G::NT, 32> BL;
     BL bl;
@@ -214,7 +215,9 @@ __device__ __forceinline__ void gemm2_task(const FwdParams& p, const RowTile rt,
         bl.bp = p.w_down + (((size_t)rt.expert * I + BL::TG::k0()) * d + c) * 2;
     }
     f32x16_t acc[8];
-    mma_mainloop<NW>(al, bl, I / BK, smem, wave * 32 < rt.rows, acc);
+    mma_mainloop_direct<NW>(al, bl, I / BK, smem, wave * 32 < rt.rows, acc);
+    PROF_ADD(TASK_GEMM2, 2, PROF_NOW() - t_start);
+    PROF_ADD(TASK_GEMM2, 5, I / BK);
     const int col = n0 + (lane & 31) * 8;
     if (col < d) {
 #pragma unroll
@@ -281,12 +284,14 @@ fwd_worker_kernel(FwdParams p, int phase) {
     const int home = xcc_id();
     unsigned exhausted = 0;
     for (;;) {
+        const long long t_f0 = PROF_NOW();
         if (threadIdx.x == 0)
             s_task = fetch_task(ctrl, pass, home, exhausted, phase != TASK_COMBINE,
                                 phase < 0 || phase == TASK_COMBINE);
         __syncthreads();
         const int id = s_task;
         if (id == kFetchDone) break;
+        const long long t_f1 = PROF_NOW();
         if (id >= 0) {
             const Task task = p.tasks[id];
             const int type = task.type_ct >> 20, ct = task.type_ct & 0xfffff;
@@ -294,18 +299,31 @@ fwd_worker_kernel(FwdParams p, int phase) {
                 // staged launch: another phase's task, nothing to do
             } else if (type == TASK_GEMM1) {
                 const RowTile rt = p.rt[task.rt];
+                const long long t_t0 = PROF_NOW();
                 gemm1_task<NW>(p, rt, ct, smem);
                 __syncthreads();   // all h stores of the tile are complete at workgroup scope
                 if (threadIdx.x == 0) add_release(p.flag1 + task.rt, 1);
+                PROF_ADD(TASK_GEMM1, 0, t_f1 - t_f0);
+                PROF_ADD(TASK_GEMM1, 1, t_t0 - t_f1);
+                PROF_ADD(TASK_GEMM1, 3, PROF_NOW() - t_t0);
+                PROF_ADD(TASK_GEMM1, 4, 1);
+                PROF_ADD(TASK_GEMM1, 6, rt.rows);
             } else {
                 if (threadIdx.x == 0) s_ok = wait_ge(p.flag1 + task.rt, p.nct1, ctrl, p.spin_ticks);
                 __syncthreads();
+                const long long t_t0 = PROF_NOW();
+                RowTile rt = {0, 0, 0, 0};
                 if (s_ok) {
-                    const RowTile rt = p.rt[task.rt];
+                    rt = p.rt[task.rt];
                     gemm2_task<NW>(p, rt, ct, smem);
                 }
                 __syncthreads();
                 if (threadIdx.x == 0) add_release(ctrl + CTRL_DONE, 1);
+                PROF_ADD(TASK_GEMM2, 0, t_f1 - t_f0);
+                PROF_ADD(TASK_GEMM2, 1, t_t0 - t_f1);
+                PROF_ADD(TASK_GEMM2, 3, PROF_NOW() - t_t0);
+                PROF_ADD(TASK_GEMM2, 4, 1);
+                PROF_ADD(TASK_GEMM2, 6, rt.rows);
             }
         } else {
             if (threadIdx.x == 0) s_ok = wait_ge(ctrl + CTRL_DONE, ctrl[CTRL_NWAIT], ctrl, p.spin_ticks);
@@ -418,5 +436,18 @@ int fwd_launch(const moe_shape_t& s, const void* x, const void* w_gate, const vo
     return nw == 4 ? fwd_launch_nw<4>(p, opts, st) : fwd_launch_nw<8>(p, opts, st);
 }
 
+
+#ifdef UNIEP_PROFILE
+extern "C" int moe_debug_prof(unsigned long long* out, int reset) {
+    if (hipDeviceSynchronize() != hipSuccess) return MOE_ERR_HIP;
+    if (hipMemcpyFromSymbol(out, HIP_SYMBOL(g_prof), sizeof(unsigned long long) * 24) != hipSuccess)
+        return MOE_ERR_HIP;
+    if (reset) {
+        unsigned long long z[24] = {};
+        if (hipMemcpyToSymbol(HIP_SYMBOL(g_prof), z, sizeof(z)) != hipSuccess) return MOE_ERR_HIP;
+    }
+    return MOE_OK;
+}
+#endif
 
 }  // namespace uniep

@@ -43,7 +43,7 @@ struct Geom {
     // NW = 8: one workgroup per CU with two LDS stages.  NW = 4: one LDS stage (55 KB) so that
     // two workgroups share a CU and each hides the other's barriers, prologue and epilogue.
     static constexpr int NSTAGE = (NW == 8) ? 2 : 1;
-    static constexpr int SMEM = NSTAGE * STAGE;
+    static constexpr int SMEM = (NSTAGE * STAGE > 2 * B_BYTES) ? NSTAGE * STAGE : 2 * B_BYTES;
     static constexpr int WAVES_PER_SIMD = 2;
 };
 
@@ -146,7 +146,11 @@ __device__ __forceinline__ void transpose_store(const u32x4_t (&in)[KR], char* d
 #pragma unroll
         for (int p = 0; p < KR / 2; ++p) {
             const uint32_t lo = in[2 * p][j >> 1], hi = in[2 * p + 1][j >> 1];
+#ifdef UNIEP_X_NOTRANS   // timing experiments only (wrong results)
+            o[p] = (j & 1) ? lo : hi;
+#else
             o[p] = (j & 1) ? ((lo >> 16) | (hi & 0xffff0000u)) : ((lo & 0xffffu) | (hi << 16));
+#endif
         }
         char* d = dst + j * row_stride;
         if (KR == 8) *(u32x4_t*)d = u32x4_t{o[0], o[1], o[2], o[3]};
@@ -179,6 +183,9 @@ struct StridedLoader {
     // the transpose needs all k-rows of the block: the whole stage moves in part 0
     __device__ __forceinline__ void gload_part(int s, int part) {
         if (part != 0) return;
+#ifdef UNIEP_X_NOBLOAD   // timing experiments only (wrong results)
+        if (s > 1) return;
+#endif
         const char* p = bp + (size_t)UNIEP_STAGE_OF(s) * BK * ld_bytes;
 #pragma unroll
         for (int r = 0; r < TG::KR; ++r) reg[r] = *(const u32x4_t*)(p + r * ld_bytes);
@@ -394,6 +401,105 @@ __device__ __forceinline__ void mma_mainloop(AL& al, BL& bl, int nk, char* smem,
 #pragma unroll
             for (int f = 0; f < 8; ++f)
                 acc[f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b[f], acc[f], 0, 0, 0);
+        }
+        __syncthreads();
+    }
+}
+
+// ------------------------------------------------- A operand straight to registers
+// In the row-tile GEMMs every wave owns its 32 rows alone, so the A operand need
+// not pass through LDS: lane (row = lane%32, g = lane/32) fetches its fragments
+// directly, 16 bytes per k-sub-step.  The order of k inside a stage is free as
+// long as both operands agree, so lane half g takes the k-range [32g, 32g+32) of
+// the stage (64 contiguous bytes per lane and stage); the B fragment reads use the
+// same k offsets.  Four rolling fragment registers: fragment kk of stage t+1 is
+// requested right after fragment kk of stage t was consumed.
+// rp = address of (this lane's row, k = 32*g) of stage 0; rows outside the tile
+// alias a valid row.  SCALE: multiply by a per-row fp32 factor, round to bf16.
+template <bool SCALE>
+struct DirectRowLoader {
+    const char* rp;
+    float sc;
+    u32x4_t frag[BK / 16];
+
+    __device__ __forceinline__ void load(int s, int kk) {
+#ifdef UNIEP_X_NOALOAD   // timing experiments only (wrong results)
+        if (s > 0) return;
+#endif
+        frag[kk] = *(const u32x4_t*)(rp + (size_t)UNIEP_STAGE_OF(s) * (BK * 2) + kk * 16);
+    }
+    __device__ __forceinline__ bf16x8_t get(int kk) const {
+        u32x4_t r = frag[kk];
+        if (SCALE) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) r[q] = pack_bf16x2(bf16_lo(r[q]) * sc, bf16_hi(r[q]) * sc);
+        }
+        return __builtin_bit_cast(bf16x8_t, r);
+    }
+};
+
+// Main loop with the A operand in registers and only B in LDS (two stages of
+// B_BYTES at the start of smem).  Same pipeline as mma_mainloop for B.
+template <int NW, bool SCALE, class BL>
+__device__ __forceinline__ void mma_mainloop_direct(DirectRowLoader<SCALE>& al, BL& bl, int nk,
+                                                    char* smem, bool active, f32x16_t (&acc)[8]) {
+    typedef Geom<NW> G;
+    const int lane = threadIdx.x & 63;
+#pragma unroll
+    for (int f = 0; f < 8; ++f)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[f][v] = 0.f;
+    if (nk <= 0) return;
+    const bool active_u = __builtin_amdgcn_readfirstlane((int)active) != 0;
+
+#pragma unroll
+    for (int part = 0; part < 4; ++part) bl.gload_part(0, part);
+    if (active_u) {
+#pragma unroll
+        for (int kk = 0; kk < BK / 16; ++kk) al.load(0, kk);
+    }
+#pragma unroll
+    for (int part = 0; part < 4; ++part) bl.sstore_part(smem, part);
+    const int s1 = min(1, nk - 1);
+#pragma unroll
+    for (int part = 0; part < 4; ++part) bl.gload_part(s1, part);
+    __syncthreads();
+    // B fragment f of this lane: LDS row f*32 + lane%32, k bytes (lane/32)*64 + kk*16
+    const int b_off = (lane & 31) * kRowBytes + (lane >> 5) * 64;
+    if (!active_u) {
+        for (int t = 0; t < nk; ++t) {
+            char* nxt = smem + ((t + 1) & 1) * G::B_BYTES;
+            const int s2 = min(t + 2, nk - 1);
+#pragma unroll
+            for (int part = 0; part < 4; ++part) {
+                bl.sstore_part(nxt, part);
+                bl.gload_part(s2, part);
+            }
+            __syncthreads();
+        }
+        return;
+    }
+    for (int t = 0; t < nk; ++t) {
+        char* cur = smem + (t & 1) * G::B_BYTES;
+        char* nxt = smem + ((t + 1) & 1) * G::B_BYTES;
+        const int s2 = min(t + 2, nk - 1);
+        const int sa = min(t + 1, nk - 1);
+#pragma unroll
+        for (int kk = 0; kk < BK / 16; ++kk) {
+            __builtin_amdgcn_sched_barrier(0);
+            bl.sstore_part(nxt, kk);
+            bl.gload_part(s2, kk);
+            __builtin_amdgcn_sched_barrier(0);
+            bf16x8_t b[8];
+#pragma unroll
+            for (int f = 0; f < 8; ++f)
+                b[f] = *(const bf16x8_t*)(cur + b_off + f * 32 * kRowBytes + kk * 16);
+            const bf16x8_t a = al.get(kk);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int f = 0; f < 8; ++f)
+                acc[f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b[f], acc[f], 0, 0, 0);
+            al.load(sa, kk);
         }
         __syncthreads();
     }
