@@ -25,6 +25,17 @@ def max_abs(got, want):
         if np.size(got) else 0.0
 
 
+def max_abs_beyond_ulp(got, want):
+    """Largest |got - want| after allowing one bf16 unit in the last place of the reference
+    element (2^-7 |want| bounds it): both sides are bf16 values, so wherever the output exceeds
+    ~2.5 in magnitude the smallest possible disagreement already exceeds an absolute 2e-2."""
+    got = np.asarray(got, np.float64)
+    want = np.asarray(want, np.float64)
+    if got.size == 0:
+        return 0.0
+    return float(np.maximum(np.abs(got - want) - 2.0 ** -7 * np.abs(want), 0.0).max())
+
+
 def to_f64(t):
     return t.detach().float().cpu().double().numpy()
 

