@@ -56,6 +56,7 @@ struct BwdParams {
     int nct_dh, nct_dxp;        // column tiles of phase 0 (256 of I) and phase 2 (256 of d)
     int mt_dwd, nt_dwd;         // dW_down tiles per expert: ceil(I/256) x ceil(d/256)
     int mt_dwgu, nt_dwgu;       // dW_gate/up tiles per expert: ceil(d/256) x ceil(I/128)
+    int workers;                // workgroups of the worker launch (the tail waits for all of them)
     long long spin_ticks;
 };
 
@@ -154,7 +155,7 @@ __global__ void __launch_bounds__(1024) bwd_prologue_kernel(BwdParams p) {
         int v = 0;
         if (e == CTRL_NRT) v = nrt;
         if (e == CTRL_NTAIL) v = (p.s.T + kDxTokens - 1) / kDxTokens;
-        if (e == CTRL_NWAIT) v = nrt * p.nct_dxp;
+        if (e == CTRL_NWAIT) v = p.workers;
         if (e >= CTRL_QLEN && e < CTRL_QLEN + kQueues) v = s_qbase[e - CTRL_QLEN + 1] - s_qbase[e - CTRL_QLEN];
         if (e >= CTRL_QBASE && e < CTRL_QBASE + kQueues) v = s_qbase[e - CTRL_QBASE];
         p.ctrl[e] = v;
@@ -402,13 +403,21 @@ bwd_worker_kernel(BwdParams p, int phase) {
     int* ctrl = p.ctrl;
     const int pass = phase < 0 ? 0 : 1 + phase;
     const int home = xcc_id();
+    const bool use_lists = phase != B_DX;
+    const bool use_tail = phase < 0 || phase == B_DX;
+    // this launch runs dXp tiles: its workers publish their rows once, when they run out of GEMM work
+    const bool publishes = phase < 0 || phase == B_DXP;
+    bool arrived = false;
     unsigned exhausted = 0;
+    if (threadIdx.x == 0) s_task = fetch_task(ctrl, pass, home, exhausted, use_lists, use_tail);
+    __syncthreads();
     for (;;) {
-        if (threadIdx.x == 0)
-            s_task = fetch_task(ctrl, pass, home, exhausted, phase != B_DX, phase < 0 || phase == B_DX);
-        __syncthreads();
         const int id = s_task;
         if (id == kFetchDone) break;
+        PendingFetch pf;
+        pf.q = -1;
+        pf.id = 0;
+        if (threadIdx.x == 0) pf = fetch_issue(ctrl, pass, home, exhausted, use_lists);
         if (id >= 0) {
             const Task task = p.tasks[id];
             const int type = task.type_ct >> 20, ct = task.type_ct & 0xfffff;
@@ -431,8 +440,6 @@ bwd_worker_kernel(BwdParams p, int phase) {
                     const RowTile rt = p.rt[task.rt];
                     dxp_task<NW>(p, rt, ct, smem);
                 }
-                __syncthreads();
-                if (threadIdx.x == 0) add_release(ctrl + CTRL_DONE, 1);
             } else {
                 const int e = task.rt / p.mt_dwgu;
                 if (threadIdx.x == 0) s_ok = wait_ge(p.flag_e + e, p.need_e[e], ctrl, p.spin_ticks);
@@ -440,11 +447,23 @@ bwd_worker_kernel(BwdParams p, int phase) {
                 if (s_ok) dwgu_task<NW>(p, e, task.rt % p.mt_dwgu, ct, smem);
             }
         } else {
-            if (threadIdx.x == 0) s_ok = wait_ge(ctrl + CTRL_DONE, ctrl[CTRL_NWAIT], ctrl, p.spin_ticks);
+            if (publishes && !arrived) {
+                arrived = true;
+                __syncthreads();
+                if (threadIdx.x == 0) add_release(ctrl + CTRL_DONE, 1);
+            }
+            if (threadIdx.x == 0)
+                s_ok = wait_ge(ctrl + CTRL_DONE, ctrl[CTRL_NWAIT], ctrl, p.spin_ticks, CTRL_TAIL_WAIT_TICKS);
             __syncthreads();
             if (s_ok) dx_task<NW>(p, -1 - id);
         }
         __syncthreads();
+        if (threadIdx.x == 0) s_task = fetch_finish(pf, ctrl, pass, home, exhausted, use_lists, use_tail);
+        __syncthreads();
+    }
+    if (publishes && !arrived) {
+        __syncthreads();
+        if (threadIdx.x == 0) add_release(ctrl + CTRL_DONE, 1);
     }
 }
 
@@ -516,6 +535,7 @@ static int bwd_launch_nw(BwdParams& p, const moe_opts_t& opts, hipStream_t st) {
     int rc = bwd_resident_workers<NW>(&resident);
     if (rc != MOE_OK) return rc;
     const int workers = opts.workers > 0 ? min(opts.workers, resident) : resident;
+    p.workers = workers;
     const int A_cap = p.s.T * p.s.k;
     if (A_cap > 0)
         hipLaunchKernelGGL(row_meta_kernel, dim3((A_cap + 255) / 256), dim3(256), 0, st, p);

@@ -39,7 +39,11 @@ __device__ __forceinline__ int ld_relaxed(const int* p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ __forceinline__ void add_release(int* p, int v) {
+#ifdef UNIEP_X_NORELEASE   // timing experiments only
+    __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#else
     __hip_atomic_fetch_add(p, v, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+#endif
 }
 
 // ---- work queues -----------------------------------------------------------
@@ -64,6 +68,7 @@ enum CtrlWord {
     CTRL_NWAIT = 3,    // completions the tail tasks wait for
     CTRL_DONE = 4,     // completion counter of the last GEMM phase
     CTRL_WAIT_TICKS = 5,   // sum over workers of 10 ns ticks spent in scoreboard waits (diagnostic)
+    CTRL_TAIL_WAIT_TICKS = 6,   // the same for the waits of the tail tasks
     CTRL_QLEN = 8,     // [8]  entries per list
     CTRL_QBASE = 16,   // [8]  first entry of each list in the task array
     CTRL_CURSOR = 24,  // [kPasses][kQueues + 1]  list cursors and tail cursor per pass
@@ -101,6 +106,40 @@ __device__ __forceinline__ int fetch_task(int* ctrl, int pass, int home, unsigne
     return kFetchDone;
 }
 
+// Split fetch, so that the round trip of the cursor atomic overlaps with the
+// current task: fetch_issue() is called (by one thread) before the task runs and
+// only issues the atomic on the first list not yet seen empty; fetch_finish()
+// after the task turns the result into the next task, falling back to the
+// blocking walk over the remaining lists and the tail.
+struct PendingFetch {
+    int q;     // list the atomic was issued on, -1 if none
+    int id;    // value the atomic returned
+};
+__device__ __forceinline__ PendingFetch fetch_issue(int* ctrl, int pass, int home, unsigned exhausted,
+                                                    bool use_lists) {
+    PendingFetch f;
+    f.q = -1;
+    f.id = 0;
+    if (use_lists) {
+        for (int i = 0; i < kQueues; ++i) {
+            const int q = (home + i) & (kQueues - 1);
+            if (exhausted & (1u << q)) continue;
+            f.q = q;
+            f.id = atomicAdd(ctrl + CTRL_CURSOR + pass * (kQueues + 1) + q, 1);
+            break;
+        }
+    }
+    return f;
+}
+__device__ __forceinline__ int fetch_finish(const PendingFetch f, int* ctrl, int pass, int home,
+                                            unsigned& exhausted, bool use_lists, bool use_tail) {
+    if (f.q >= 0) {
+        if (f.id < ctrl[CTRL_QLEN + f.q]) return ctrl[CTRL_QBASE + f.q] + f.id;
+        exhausted |= 1u << f.q;
+    }
+    return fetch_task(ctrl, pass, home, exhausted, use_lists, use_tail);
+}
+
 // Position of expert e's producer block (pos_a) and consumer block (pos_b)
 // inside its list, given the block sizes ga[], gb[] of all experts (shared
 // memory) and the lag L >= 1: the consumer block of expert i follows the
@@ -129,6 +168,9 @@ __device__ __forceinline__ void queue_positions(const int* ga, const int* gb, in
 // producer tasks in between that a workgroup which runs ahead finds other
 // producers to do instead of waiting (about 1.5 x the workgroups of one XCD).
 __device__ __forceinline__ int queue_lag(int total_producer_tasks, int ec) {
+#ifdef UNIEP_X_LAG
+    return UNIEP_X_LAG;
+#endif
     const int per = max(1, total_producer_tasks / max(1, ec));
     return min(8, max(1, (48 + per - 1) / per));
 }
@@ -136,13 +178,14 @@ __device__ __forceinline__ int queue_lag(int total_producer_tasks, int ec) {
 // Bounded wait for *p >= need.  Returns false (and raises the status word) if
 // the bound is exceeded or another worker already raised it, so that every
 // wave leaves the kernel in finite time whatever happens.
-__device__ __forceinline__ bool wait_ge(const int* p, int need, int* ctrl, long long limit_ticks) {
+__device__ __forceinline__ bool wait_ge(const int* p, int need, int* ctrl, long long limit_ticks,
+                                        int stat_word = CTRL_WAIT_TICKS) {
     if (ld_acquire(p) >= need) return true;
     const long long t0 = wall_clock64();
     for (;;) {
         __builtin_amdgcn_s_sleep(8);
         if (ld_acquire(p) >= need) {
-            atomicAdd(ctrl + CTRL_WAIT_TICKS, (int)(wall_clock64() - t0));
+            atomicAdd(ctrl + stat_word, (int)(wall_clock64() - t0));
             return true;
         }
         if (ld_relaxed(ctrl + CTRL_STATUS) != 0) return false;

@@ -46,6 +46,7 @@ struct FwdParams {
     Task* tasks;
     int nct1, nct2;   // column tiles of GEMM1 (128 h-columns each) and GEMM2 (256 each)
     int max_rt;
+    int workers;   // workgroups of the worker launch (the tail waits for all of them)
     long long spin_ticks;
 };
 
@@ -123,7 +124,7 @@ __global__ void __launch_bounds__(1024) fwd_prologue_kernel(FwdParams p) {
         int v = 0;
         if (e == CTRL_NRT) v = nrt;
         if (e == CTRL_NTAIL) v = (p.s.T + kCombineTokens - 1) / kCombineTokens;
-        if (e == CTRL_NWAIT) v = nrt * p.nct2;
+        if (e == CTRL_NWAIT) v = p.workers;
         if (e >= CTRL_QLEN && e < CTRL_QLEN + kQueues) v = s_qbase[e - CTRL_QLEN + 1] - s_qbase[e - CTRL_QLEN];
         if (e >= CTRL_QBASE && e < CTRL_QBASE + kQueues) v = s_qbase[e - CTRL_QBASE];
         p.ctrl[e] = v;
@@ -282,16 +283,22 @@ fwd_worker_kernel(FwdParams p, int phase) {
     int* ctrl = p.ctrl;
     const int pass = phase < 0 ? 0 : 1 + phase;
     const int home = xcc_id();
+    const bool use_lists = phase != TASK_COMBINE;
+    const bool use_tail = phase < 0 || phase == TASK_COMBINE;
+    // this launch runs GEMM2 tiles: its workers publish their o rows once, when they run out of
+    // GEMM work, instead of once per tile
+    const bool publishes = phase < 0 || phase == TASK_GEMM2;
+    bool arrived = false;
     unsigned exhausted = 0;
+    if (threadIdx.x == 0) s_task = fetch_task(ctrl, pass, home, exhausted, use_lists, use_tail);
+    __syncthreads();
     for (;;) {
-        const long long t_f0 = PROF_NOW();
-        if (threadIdx.x == 0)
-            s_task = fetch_task(ctrl, pass, home, exhausted, phase != TASK_COMBINE,
-                                phase < 0 || phase == TASK_COMBINE);
-        __syncthreads();
         const int id = s_task;
         if (id == kFetchDone) break;
-        const long long t_f1 = PROF_NOW();
+        PendingFetch pf;
+        pf.q = -1;
+        pf.id = 0;
+        if (threadIdx.x == 0) pf = fetch_issue(ctrl, pass, home, exhausted, use_lists);
         if (id >= 0) {
             const Task task = p.tasks[id];
             const int type = task.type_ct >> 20, ct = task.type_ct & 0xfffff;
@@ -299,38 +306,35 @@ fwd_worker_kernel(FwdParams p, int phase) {
                 // staged launch: another phase's task, nothing to do
             } else if (type == TASK_GEMM1) {
                 const RowTile rt = p.rt[task.rt];
-                const long long t_t0 = PROF_NOW();
                 gemm1_task<NW>(p, rt, ct, smem);
                 __syncthreads();   // all h stores of the tile are complete at workgroup scope
                 if (threadIdx.x == 0) add_release(p.flag1 + task.rt, 1);
-                PROF_ADD(TASK_GEMM1, 0, t_f1 - t_f0);
-                PROF_ADD(TASK_GEMM1, 1, t_t0 - t_f1);
-                PROF_ADD(TASK_GEMM1, 3, PROF_NOW() - t_t0);
-                PROF_ADD(TASK_GEMM1, 4, 1);
-                PROF_ADD(TASK_GEMM1, 6, rt.rows);
             } else {
                 if (threadIdx.x == 0) s_ok = wait_ge(p.flag1 + task.rt, p.nct1, ctrl, p.spin_ticks);
                 __syncthreads();
-                const long long t_t0 = PROF_NOW();
-                RowTile rt = {0, 0, 0, 0};
                 if (s_ok) {
-                    rt = p.rt[task.rt];
+                    const RowTile rt = p.rt[task.rt];
                     gemm2_task<NW>(p, rt, ct, smem);
                 }
-                __syncthreads();
-                if (threadIdx.x == 0) add_release(ctrl + CTRL_DONE, 1);
-                PROF_ADD(TASK_GEMM2, 0, t_f1 - t_f0);
-                PROF_ADD(TASK_GEMM2, 1, t_t0 - t_f1);
-                PROF_ADD(TASK_GEMM2, 3, PROF_NOW() - t_t0);
-                PROF_ADD(TASK_GEMM2, 4, 1);
-                PROF_ADD(TASK_GEMM2, 6, rt.rows);
             }
         } else {
-            if (threadIdx.x == 0) s_ok = wait_ge(ctrl + CTRL_DONE, ctrl[CTRL_NWAIT], ctrl, p.spin_ticks);
+            if (publishes && !arrived) {   // first tail task: all of this worker's o rows are written
+                arrived = true;
+                __syncthreads();
+                if (threadIdx.x == 0) add_release(ctrl + CTRL_DONE, 1);
+            }
+            if (threadIdx.x == 0)
+                s_ok = wait_ge(ctrl + CTRL_DONE, ctrl[CTRL_NWAIT], ctrl, p.spin_ticks, CTRL_TAIL_WAIT_TICKS);
             __syncthreads();
             if (s_ok) combine_task<NW>(p, -1 - id);
         }
-        __syncthreads();   // s_task / s_ok are rewritten next round
+        __syncthreads();   // every thread has read s_task / s_ok of this round
+        if (threadIdx.x == 0) s_task = fetch_finish(pf, ctrl, pass, home, exhausted, use_lists, use_tail);
+        __syncthreads();
+    }
+    if (publishes && !arrived) {   // ran out of work without seeing a tail task
+        __syncthreads();
+        if (threadIdx.x == 0) add_release(ctrl + CTRL_DONE, 1);
     }
 }
 
@@ -394,6 +398,7 @@ static int fwd_launch_nw(FwdParams& p, const moe_opts_t& opts, hipStream_t st) {
     int rc = resident_workers<NW>(&resident);
     if (rc != MOE_OK) return rc;
     int workers = opts.workers > 0 ? min(opts.workers, resident) : resident;
+    p.workers = workers;
     hipLaunchKernelGGL(fwd_prologue_kernel<Geom<NW>::BM>, dim3(1), dim3(1024), 0, st, p);
     if (opts.schedule == 2) {
         for (int phase = 0; phase < 3; ++phase)

@@ -231,6 +231,7 @@ struct StridedLoaderK {
 template <int NT, int NCH, bool SCALE>
 struct GatherStridedLoader {
     typedef TrGeom<NT, NCH> TG;
+    static constexpr bool kSpread = false;   // the whole stage moves in one go (part 0)
     const char* src;
     size_t ld_bytes;
     const int32_t* row_tok;
@@ -238,20 +239,38 @@ struct GatherStridedLoader {
     int row0, K;
     u32x4_t reg[TG::KR];
     float sc[TG::KR];
+    // token ids (and gates) of the stage after the one in flight, fetched one stage early so
+    // that the data loads never wait on the index loads
+    int32_t tok_next[TG::KR];
+    float sc_next[TG::KR];
+    int next_stage;
     int lds_off, k0;
 
-    __device__ __forceinline__ void init() { lds_off = TG::lds_off(); k0 = TG::k0(); }
+    __device__ __forceinline__ void init() {
+        lds_off = TG::lds_off();
+        k0 = TG::k0();
+        next_stage = -1;
+    }
+    __device__ __forceinline__ void fetch_index(int s) {
+#pragma unroll
+        for (int r = 0; r < TG::KR; ++r) {
+            const int row = row0 + min(s * BK + k0 + r, K - 1);
+            tok_next[r] = row_tok[row];
+            if (SCALE) sc_next[r] = row_w[row];
+        }
+        next_stage = s;
+    }
     __device__ __forceinline__ void gload_part(int s, int part) {
         if (part != 0) return;
+        if (next_stage != s) fetch_index(s);   // first stage of a tile (uniform branch)
 #pragma unroll
         for (int r = 0; r < TG::KR; ++r) {
             const int k = s * BK + k0 + r;
-            const int row = row0 + min(k, K - 1);
-            const int tok = row_tok[row];
-            if (SCALE) sc[r] = row_w[row];
-            const u32x4_t v = *(const u32x4_t*)(src + (size_t)tok * ld_bytes);
+            if (SCALE) sc[r] = sc_next[r];
+            const u32x4_t v = *(const u32x4_t*)(src + (size_t)tok_next[r] * ld_bytes);
             reg[r] = (k < K) ? v : zero4();
         }
+        fetch_index(s + 1);   // row index is clamped inside: reads stay within the expert's rows
     }
     __device__ __forceinline__ void sstore_part(char* base, int part) {
         if (part != 0) return;
