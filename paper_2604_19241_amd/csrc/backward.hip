@@ -342,6 +342,7 @@ template <int NW>
 __device__ __forceinline__ void dx_task(const BwdParams& p, int block) {
     const int d = p.s.d, k = p.s.k, T = p.s.T;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const bool want_dots = p.dtopk_w != nullptr;
     for (int tt = wave; tt < kDxTokens; tt += NW) {
         const int t = block * kDxTokens + tt;
         if (t >= T) break;
@@ -352,25 +353,41 @@ __device__ __forceinline__ void dx_task(const BwdParams& p, int block) {
 #pragma unroll
         for (int j = 0; j < kMaxTopK; ++j) dots[j] = 0.f;
         for (int c = lane * 8; c < d; c += 64 * 8) {
+            // the row loads of eight slots are issued before the first is used
+            u32x4_t dyv = zero4();
+            if (want_dots) dyv = *(const u32x4_t*)(p.dy + ((size_t)t * d + c) * 2);
             float a[8];
 #pragma unroll
             for (int q = 0; q < 8; ++q) a[q] = 0.f;
-            u32x4_t dyv = zero4();
-            if (p.dtopk_w) dyv = *(const u32x4_t*)(p.dy + ((size_t)t * d + c) * 2);
 #pragma unroll
-            for (int j = 0; j < kMaxTopK; ++j) {
-                if (j < k && rows[j] >= 0) {
-                    const u32x4_t v = *(const u32x4_t*)(p.dxp + ((size_t)rows[j] * d + c) * 2);
+            for (int j0 = 0; j0 < kMaxTopK; j0 += 8) {
+                if (j0 >= k) break;
+                u32x4_t v[8], ov[8];
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        a[2 * q] += bf16_lo(v[q]);
-                        a[2 * q + 1] += bf16_hi(v[q]);
+                for (int jj = 0; jj < 8; ++jj) {
+                    const int j = j0 + jj;
+                    v[jj] = zero4();
+                    ov[jj] = zero4();
+                    if (j < k && rows[j] >= 0) {
+                        v[jj] = *(const u32x4_t*)(p.dxp + ((size_t)rows[j] * d + c) * 2);
+                        if (want_dots) ov[jj] = *(const u32x4_t*)(p.o + ((size_t)rows[j] * d + c) * 2);
                     }
-                    if (p.dtopk_w) {
-                        const u32x4_t ov = *(const u32x4_t*)(p.o + ((size_t)rows[j] * d + c) * 2);
+                }
 #pragma unroll
-                        for (int q = 0; q < 4; ++q)
-                            dots[j] += bf16_lo(dyv[q]) * bf16_lo(ov[q]) + bf16_hi(dyv[q]) * bf16_hi(ov[q]);
+                for (int jj = 0; jj < 8; ++jj) {
+                    const int j = j0 + jj;
+                    if (j < k && rows[j] >= 0) {   // slot order, local slots only
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            a[2 * q] += bf16_lo(v[jj][q]);
+                            a[2 * q + 1] += bf16_hi(v[jj][q]);
+                        }
+                        if (want_dots) {
+#pragma unroll
+                            for (int q = 0; q < 4; ++q)
+                                dots[j] += bf16_lo(dyv[q]) * bf16_lo(ov[jj][q]) +
+                                           bf16_hi(dyv[q]) * bf16_hi(ov[jj][q]);
+                        }
                     }
                 }
             }
@@ -379,7 +396,7 @@ __device__ __forceinline__ void dx_task(const BwdParams& p, int block) {
             for (int q = 0; q < 4; ++q) out[q] = pack_bf16x2(a[2 * q], a[2 * q + 1]);
             *(u32x4_t*)(p.dx + ((size_t)t * d + c) * 2) = out;
         }
-        if (p.dtopk_w) {
+        if (want_dots) {
 #pragma unroll
             for (int j = 0; j < kMaxTopK; ++j) {
                 if (j < k) {

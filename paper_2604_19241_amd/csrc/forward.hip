@@ -16,6 +16,12 @@ namespace uniep {
 
 enum TaskType { TASK_GEMM1 = 0, TASK_GEMM2 = 1, TASK_COMBINE = 2 };
 
+// Where GEMM1 stages its A operand (the gathered rows of x): 1 = straight into registers,
+// 0 = through LDS with 128-byte coalesced row pieces.
+#ifndef UNIEP_GEMM1_A_DIRECT
+#define UNIEP_GEMM1_A_DIRECT 1
+#endif
+
 #ifdef UNIEP_PROFILE   // timing experiments only: 10 ns ticks per task type {fetch, wait, main, epilogue, count}
 __device__ unsigned long long g_prof[3][8];
 #define PROF_NOW() wall_clock64()
@@ -142,12 +148,27 @@ __device__ __forceinline__ void gemm1_task(const FwdParams& p, const RowTile rt,
     typedef Geom<NW> G;
     const int d = p.s.d, I = p.s.I, k = p.s.k;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+#if UNIEP_GEMM1_A_DIRECT
     DirectRowLoader<false> al;   // dispatch = gather: each lane reads its token's row of x
     {
         const int m = min(wave * 32 + (lane & 31), rt.rows - 1);   // rows past the tile alias its last row
         const int tok = p.perm[rt.row0 + m] / k;
         al.rp = p.x + ((size_t)tok * d + (lane >> 5) * 32) * 2;
     }
+#else
+    typedef RowLoader<G::NT, G::BM, false> AL;   // dispatch = gather: 8 lanes read 128 bytes of a token's row of x
+    AL al;
+    al.init();
+    {
+        const int kc = tid & 7;
+#pragma unroll
+        for (int q = 0; q < AL::NP; ++q) {
+            const int m = min(AL::row(q), rt.rows - 1);   // rows past the tile alias its last row
+            const int tok = p.perm[rt.row0 + m] / k;
+            al.rp[q] = p.x + ((size_t)tok * d + kc * 8) * 2;
+        }
+    }
+#endif
     typedef StridedLoader<G::NT, 32> BL;
     BL bl;
     bl.init();
@@ -160,7 +181,11 @@ __device__ __forceinline__ void gemm1_task(const FwdParams& p, const RowTile rt,
         bl.bp = w + (((size_t)rt.expert * d + BL::TG::k0()) * I + hc) * 2;
     }
     f32x16_t acc[8];
+#if UNIEP_GEMM1_A_DIRECT
     mma_mainloop_direct<NW>(al, bl, d / BK, smem, wave * 32 < rt.rows, acc);
+#else
+    mma_mainloop<NW>(al, bl, d / BK, smem, wave * 32 < rt.rows, acc);
+#endif
     PROF_ADD(TASK_GEMM1, 2, PROF_NOW() - t_start);
     PROF_ADD(TASK_GEMM1, 5, d / BK);
 
@@ -247,25 +272,45 @@ __device__ __forceinline__ void combine_task(const FwdParams& p, int block) {
             rows[j] = (j < k) ? p.inv_perm[(size_t)t * k + j] : -1;
             w[j] = (j < k) ? p.topk_w[(size_t)t * k + j] : 0.f;
         }
-        for (int c = lane * 8; c < d; c += 64 * 8) {
-            float a[8];
-#pragma unroll
-            for (int q = 0; q < 8; ++q) a[q] = 0.f;
+        // two 16-byte column pieces per lane and round: all 2k row loads are issued before the
+        // first is used, so a wave keeps up to 2k KB in flight
+        for (int c0 = lane * 8; c0 < d; c0 += 2 * 64 * 8) {
+            const int c1 = c0 + 64 * 8;
+            const bool two = c1 < d;
+            u32x4_t v0[kMaxTopK], v1[kMaxTopK];
 #pragma unroll
             for (int j = 0; j < kMaxTopK; ++j) {
+                v0[j] = zero4();
+                v1[j] = zero4();
                 if (j < k && rows[j] >= 0) {
-                    const u32x4_t ov = *(const u32x4_t*)(p.o + ((size_t)rows[j] * d + c) * 2);
+                    const char* src = p.o + (size_t)rows[j] * d * 2;
+                    v0[j] = *(const u32x4_t*)(src + (size_t)c0 * 2);
+                    if (two) v1[j] = *(const u32x4_t*)(src + (size_t)c1 * 2);
+                }
+            }
+            float a0[8], a1[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) a0[q] = a1[q] = 0.f;
+#pragma unroll
+            for (int j = 0; j < kMaxTopK; ++j) {
+                if (j < k && rows[j] >= 0) {   // slot order, local slots only
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
-                        a[2 * q] += w[j] * bf16_lo(ov[q]);
-                        a[2 * q + 1] += w[j] * bf16_hi(ov[q]);
+                        a0[2 * q] += w[j] * bf16_lo(v0[j][q]);
+                        a0[2 * q + 1] += w[j] * bf16_hi(v0[j][q]);
+                        a1[2 * q] += w[j] * bf16_lo(v1[j][q]);
+                        a1[2 * q + 1] += w[j] * bf16_hi(v1[j][q]);
                     }
                 }
             }
-            u32x4_t yv;
+            u32x4_t y0, y1;
 #pragma unroll
-            for (int q = 0; q < 4; ++q) yv[q] = pack_bf16x2(a[2 * q], a[2 * q + 1]);
-            *(u32x4_t*)(p.y + ((size_t)t * d + c) * 2) = yv;
+            for (int q = 0; q < 4; ++q) {
+                y0[q] = pack_bf16x2(a0[2 * q], a0[2 * q + 1]);
+                y1[q] = pack_bf16x2(a1[2 * q], a1[2 * q + 1]);
+            }
+            *(u32x4_t*)(p.y + ((size_t)t * d + c0) * 2) = y0;
+            if (two) *(u32x4_t*)(p.y + ((size_t)t * d + c1) * 2) = y1;
         }
     }
 }
