@@ -7,7 +7,9 @@ workload has a backward).  Prints ONE JSON line:
 
   value       useful TFLOP/s of the whole step (6*A*d*I forward + 12*A*d*I
               backward, A = realised routed rows) -- the metric the benchmark spec names
-  roofline    the forward MegaKernel against the bf16 dense MFMA peak
+  roofline    the dominant kernel (the backward MegaKernel when the workload has a
+              backward, else the forward MegaKernel) against the bf16 dense MFMA peak;
+              roofline_forward carries the forward MegaKernel beside it
   cpu_baseline  the CPU oracle timed on a bounded sample of the same workload
 
 Usage: python bench.py [--gpus 1] [--steps K] [--warmup W] [--config N]
@@ -41,6 +43,9 @@ def parse():
     ap.add_argument("--no-backward", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    ap.add_argument("--calibration-copy-mib", type=int, default=0,
+                    help="also launch the plain copy kernel on this many MiB, 5 times "
+                         "(scale for the HBM byte counters of a rocprofv3 --pmc run)")
     return ap.parse_args()
 
 
@@ -57,6 +62,19 @@ def event_ms(fn, n):
     torch.cuda.synchronize()
     ts = sorted(a.elapsed_time(b) for a, b in evs)
     return sum(ts) / len(ts), ts[len(ts) // 2], ts[0]
+
+
+def measured_traffic(cfg_name, kernel):
+    """HBM bytes per launch of `kernel` from the committed counter summary
+    (profiles/hbm_traffic_<workload>.txt, written by paper_2604_19241_amd.profile_summary
+    from a FETCH_SIZE and a WRITE_SIZE run scaled by the calibration copy), or None."""
+    path = ROOT / "profiles" / f"hbm_traffic_{cfg_name.replace('-', '_')}.txt"
+    if not path.exists():
+        return None
+    for line in path.read_text().splitlines():
+        if line.startswith(kernel) and "traffic_bytes_per_launch=" in line:
+            return float(line.split("traffic_bytes_per_launch=")[1].split()[0])
+    return None
 
 
 def cpu_baseline(cfg, inp, has_bwd, budget_s):
@@ -143,6 +161,14 @@ def main():
         if has_bwd:
             bwd()
 
+    if args.calibration_copy_mib > 0:
+        src = torch.zeros(args.calibration_copy_mib << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            moe.moe_calibration_copy(dst, src)
+        torch.cuda.synchronize()
+        del src, dst
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -165,16 +191,27 @@ def main():
     ms_fwd = event_ms(fwd, n)
     ms_bwd = event_ms(bwd, n) if has_bwd else None
     fwd_tflops = f_fwd / (ms_fwd[0] * 1e-3) / 1e12
-    roofline = {
-        "kernel": "fwd_worker_kernel (forward MegaKernel, incl. its 1-block prologue launch)",
-        "bound": "mfma",
-        "achieved": fwd_tflops,
-        "peak": MFMA_BF16_PEAK_TFLOPS,
-        "unit": "TFLOP/s",
-        "frac": fwd_tflops / MFMA_BF16_PEAK_TFLOPS,
-        "traffic": None,
-        "avg_ms": ms_fwd[0], "median_ms": ms_fwd[1], "min_ms": ms_fwd[2],
-    }
+    # waves per workgroup the library picks (tile height 32 * nw): 8 from 160 rows per expert up
+    nw = {128: 4, 256: 8}.get(args.tile_rows, 8 if cfg.T * cfg.k / cfg.E >= 160.0 else 4)
+
+    def roof(kernel, what, flops, ms):
+        tf = flops / (ms[0] * 1e-3) / 1e12
+        return {
+            "kernel": f"{kernel} ({what}; the HIP events also span its small prologue launches)",
+            "bound": "mfma",
+            "achieved": tf,
+            "peak": MFMA_BF16_PEAK_TFLOPS,
+            "unit": "TFLOP/s",
+            "frac": tf / MFMA_BF16_PEAK_TFLOPS,
+            "traffic": measured_traffic(cfg.name, kernel),
+            "flops_per_launch": flops,
+            "avg_ms": ms[0], "median_ms": ms[1], "min_ms": ms[2],
+        }
+
+    roof_fwd = roof(f"fwd_worker_kernel<{nw}>", "forward MegaKernel, 6*A*d*I flop per launch", f_fwd, ms_fwd)
+    roof_bwd = roof(f"bwd_worker_kernel<{nw}>", "backward MegaKernel, 12*A*d*I flop per launch",
+                    f_bwd, ms_bwd) if has_bwd else None
+    roofline = roof_bwd if has_bwd else roof_fwd
     counts = state["r"].counts.cpu().tolist()
     out = {
         "metric": "fused MoE fwd+bwd TFLOP/s" if has_bwd else "fused MoE fwd TFLOP/s",
@@ -202,6 +239,8 @@ def main():
         "expert_load": moe_synth.histogram_summary(counts),
         "roofline": roofline,
     }
+    if has_bwd:
+        out["roofline_forward"] = roof_fwd
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, inp, has_bwd, args.cpu_seconds)
     print(json.dumps(out), flush=True)

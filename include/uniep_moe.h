@@ -152,6 +152,13 @@ int moe_device_status(const void* ws, void* stream);
 /* Static string for a return code. */
 const char* moe_status_string(int code);
 
+/* Measurement aid, not part of the MoE path: copies `bytes` (a multiple of 16)
+ * from src to dst (device pointers, 16-byte aligned, not overlapping) with one
+ * plain streaming kernel, `calibration_copy_kernel`.  Its known traffic (bytes
+ * read, bytes written) is what the HBM byte counters of a profiler run are
+ * scaled by.  Returns MOE_ERR_ARG for a NULL/misaligned pointer or size. */
+int moe_calibration_copy(void* dst, const void* src, size_t bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -19,7 +19,7 @@ MOE_OK = 0
 MOE_ERR_ARG, MOE_ERR_SHAPE, MOE_ERR_WORKSPACE, MOE_ERR_HIP, MOE_ERR_DEVICE = -1, -2, -3, -4, -5
 
 EXPORTS = ("moe_workspace_bytes", "moe_saved_layout", "moe_route", "moe_fused_forward",
-           "moe_fused_backward", "moe_device_status", "moe_status_string")
+           "moe_fused_backward", "moe_device_status", "moe_status_string", "moe_calibration_copy")
 
 
 class MoEShape(ctypes.Structure):
@@ -193,6 +193,17 @@ def moe_fused_backward(shape: MoEShape, dy, x, w_gate, w_up, w_down, routing: Ro
 
 def moe_device_status(ws: torch.Tensor) -> int:
     return int(load_library().moe_device_status(_ptr(ws), _stream(ws.device)))
+
+
+def moe_calibration_copy(dst: torch.Tensor, src: torch.Tensor) -> None:
+    """Plain streaming copy kernel of known traffic (profiler counter calibration)."""
+    assert dst.is_cuda and src.is_cuda and dst.is_contiguous() and src.is_contiguous()
+    nbytes = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() == nbytes
+    lib = load_library()
+    lib.moe_calibration_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    _check(lib.moe_calibration_copy(_ptr(dst), _ptr(src), nbytes, _stream(src.device)),
+           "moe_calibration_copy")
 
 
 def alloc_saved(shape: MoEShape, device) -> torch.Tensor:

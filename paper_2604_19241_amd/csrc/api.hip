@@ -2,6 +2,8 @@
 // Every check happens before anything is enqueued.
 #include "common.hpp"
 
+#include <algorithm>
+
 namespace uniep {
 size_t route_workspace_bytes(const moe_shape_t& s);
 int route_launch(const moe_shape_t& s, const float* logits, const moe_routing_t& out, void* ws,
@@ -80,7 +82,26 @@ SavedLayout saved_layout(const moe_shape_t& s) {
 
 }  // namespace
 
+// Plain streaming copy with known HBM traffic (profiler counter calibration).
+__global__ void __launch_bounds__(256) calibration_copy_kernel(uniep::u32x4_t* __restrict__ dst,
+                                                               const uniep::u32x4_t* __restrict__ src,
+                                                               size_t n16) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride)
+        __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
+}
+
 extern "C" {
+
+int moe_calibration_copy(void* dst, const void* src, size_t bytes, void* stream) {
+    if (!dst || !src || ((uintptr_t)dst & 15) || ((uintptr_t)src & 15) || (bytes & 15)) return MOE_ERR_ARG;
+    if (bytes == 0) return MOE_OK;
+    const size_t n16 = bytes / 16;
+    const int grid = (int)std::min<size_t>((n16 + 255) / 256, 256 * 16);
+    hipLaunchKernelGGL(calibration_copy_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream,
+                       (uniep::u32x4_t*)dst, (const uniep::u32x4_t*)src, n16);
+    return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
+}
 
 int moe_workspace_bytes(const moe_shape_t* shape, size_t* route_ws, size_t* fwd_ws, size_t* bwd_ws,
                         size_t* saved_bytes) {

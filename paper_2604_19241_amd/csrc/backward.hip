@@ -86,6 +86,7 @@ __global__ void __launch_bounds__(1024) bwd_prologue_kernel(BwdParams p) {
     __shared__ int32_t s_ta[kMaxExperts];
     __shared__ int32_t s_tb[kMaxExperts];
     __shared__ int32_t s_qbase[kQueues + 1];
+    __shared__ int32_t s_qlen[kQueues];
     __shared__ int32_t s_lag;
     const int e = threadIdx.x;
     const int ec = p.s.e_count;
@@ -106,16 +107,20 @@ __global__ void __launch_bounds__(1024) bwd_prologue_kernel(BwdParams p) {
         __syncthreads();
     }
     const int nrt = s_scan[kMaxExperts - 1];
+    if (e < kQueues) {   // length of list e
+        int len = 0;
+        for (int j = e; j < ec; j += kQueues) len += s_ga[j] + s_gb[j];
+        s_qlen[e] = len;
+    }
+    __syncthreads();
     if (e == 0) {
         int base = 0;
         for (int q = 0; q < kQueues; ++q) {
             s_qbase[q] = base;
-            for (int j = q; j < ec; j += kQueues) base += s_ga[j] + s_gb[j];
+            base += s_qlen[q];
         }
         s_qbase[kQueues] = base;
-        int tot = 0;
-        for (int j = 0; j < ec; ++j) tot += s_ga[j];
-        s_lag = queue_lag(tot, ec);
+        s_lag = queue_lag(nrt * p.nct_dh + ec * per_dwd, ec);
     }
     __syncthreads();
     if (e < ec) {
@@ -139,16 +144,16 @@ __global__ void __launch_bounds__(1024) bwd_prologue_kernel(BwdParams p) {
         s_tb[e] = s_qbase[e & (kQueues - 1)] + pb;
     }
     __syncthreads();
-    for (int x = 0; x < ec; ++x) {
-        const int rt0 = s_rt0[x];
+    for (int x = e >> 6; x < ec; x += 16) {   // one wave writes the two blocks of an expert
+        const int rt0 = s_rt0[x], lane = e & 63;
         const int n_dh = s_ga[x] - per_dwd, n_dxp = s_gb[x] - per_dwgu;
         Task* ta = p.tasks + s_ta[x];
         Task* tb = p.tasks + s_tb[x];
-        for (int i = e; i < n_dh; i += 1024) ta[i] = Task{rt0 + i / p.nct_dh, (B_DH << 20) | (i % p.nct_dh)};
-        for (int i = e; i < per_dwd; i += 1024)
+        for (int i = lane; i < n_dh; i += 64) ta[i] = Task{rt0 + i / p.nct_dh, (B_DH << 20) | (i % p.nct_dh)};
+        for (int i = lane; i < per_dwd; i += 64)
             ta[n_dh + i] = Task{x * p.mt_dwd + i / p.nt_dwd, (B_DWD << 20) | (i % p.nt_dwd)};
-        for (int i = e; i < n_dxp; i += 1024) tb[i] = Task{rt0 + i / p.nct_dxp, (B_DXP << 20) | (i % p.nct_dxp)};
-        for (int i = e; i < per_dwgu; i += 1024)
+        for (int i = lane; i < n_dxp; i += 64) tb[i] = Task{rt0 + i / p.nct_dxp, (B_DXP << 20) | (i % p.nct_dxp)};
+        for (int i = lane; i < per_dwgu; i += 64)
             tb[n_dxp + i] = Task{x * p.mt_dwgu + i / p.nt_dwgu, (B_DWGU << 20) | (i % p.nt_dwgu)};
     }
     if (e < CTRL_WORDS) {

@@ -66,6 +66,7 @@ __global__ void __launch_bounds__(1024) fwd_prologue_kernel(FwdParams p) {
     __shared__ int32_t s_g1[kMaxExperts];
     __shared__ int32_t s_g2[kMaxExperts];
     __shared__ int32_t s_qbase[kQueues + 1];
+    __shared__ int32_t s_qlen[kQueues];
     __shared__ int32_t s_lag;
     const int e = threadIdx.x;
     const int ec = p.s.e_count;
@@ -85,16 +86,20 @@ __global__ void __launch_bounds__(1024) fwd_prologue_kernel(FwdParams p) {
         __syncthreads();
     }
     const int nrt = s_scan[kMaxExperts - 1];
+    if (e < kQueues) {   // length of list e
+        int len = 0;
+        for (int j = e; j < ec; j += kQueues) len += s_g1[j] + s_g2[j];
+        s_qlen[e] = len;
+    }
+    __syncthreads();
     if (e == 0) {
         int base = 0;
         for (int q = 0; q < kQueues; ++q) {
             s_qbase[q] = base;
-            for (int j = q; j < ec; j += kQueues) base += s_g1[j] + s_g2[j];
+            base += s_qlen[q];
         }
         s_qbase[kQueues] = base;
-        int tot = 0;
-        for (int j = 0; j < ec; ++j) tot += s_g1[j];
-        s_lag = queue_lag(tot, ec);
+        s_lag = queue_lag(nrt * p.nct1, ec);
     }
     __syncthreads();
     __shared__ int32_t s_rt0[kMaxExperts];
@@ -119,12 +124,13 @@ __global__ void __launch_bounds__(1024) fwd_prologue_kernel(FwdParams p) {
         s_t2[e] = s_qbase[e & (kQueues - 1)] + pos2;
     }
     __syncthreads();
-    for (int x = 0; x < ec; ++x) {   // all threads write each expert's two blocks
-        const int rt0 = s_rt0[x];
+    for (int x = e >> 6; x < ec; x += 16) {   // one wave writes the two blocks of an expert
+        const int rt0 = s_rt0[x], lane = e & 63;
         Task* t1 = p.tasks + s_t1[x];
         Task* t2 = p.tasks + s_t2[x];
-        for (int i = e; i < s_g1[x]; i += 1024) t1[i] = Task{rt0 + i / p.nct1, (TASK_GEMM1 << 20) | (i % p.nct1)};
-        for (int i = e; i < s_g2[x]; i += 1024) t2[i] = Task{rt0 + i / p.nct2, (TASK_GEMM2 << 20) | (i % p.nct2)};
+        const int n1 = s_g1[x], n2 = s_g2[x];
+        for (int i = lane; i < n1; i += 64) t1[i] = Task{rt0 + i / p.nct1, (TASK_GEMM1 << 20) | (i % p.nct1)};
+        for (int i = lane; i < n2; i += 64) t2[i] = Task{rt0 + i / p.nct2, (TASK_GEMM2 << 20) | (i % p.nct2)};
     }
     if (e < CTRL_WORDS) {
         int v = 0;
