@@ -100,15 +100,44 @@ chunk_count_kernel(const int32_t* __restrict__ topk_idx, int F, int e_start, int
 // ------------------------------------------- scan over chunks, then over experts
 // One workgroup.  In place: chunk_cnt[c][e] becomes the number of e-slots in
 // chunks before c.  counts[e] = total, offsets = exclusive CumSum(counts).
+// The chunks are cut into G = 1024 / e_pad contiguous groups (e_pad = e_count
+// rounded up to a power of two); thread (g, e) first sums its group, the group
+// sums are scanned over g, then the thread rewrites its chunks with the running value.
 __global__ void __launch_bounds__(1024)
 scan_kernel(int32_t* __restrict__ chunk_cnt, int n_chunks, int e_count,
             int32_t* __restrict__ counts, int32_t* __restrict__ offsets) {
     __shared__ int32_t s_tot[kMaxExperts];
-    const int e = threadIdx.x;
-    int32_t run = 0;
+    __shared__ int32_t s_grp[kMaxExperts];   // [G][e_pad]
+    const int tid = threadIdx.x;
+    int e_pad = 1;
+    while (e_pad < e_count) e_pad <<= 1;
+    const int G = kMaxExperts / e_pad;
+    const int e = tid & (e_pad - 1), g = tid / e_pad;
+    const int per = (n_chunks + G - 1) / G;
+    const int c0 = min(g * per, n_chunks), c1 = min(c0 + per, n_chunks);
+    int32_t sum = 0;
     if (e < e_count) {
-        int c = 0;
-        for (; c + 8 <= n_chunks; c += 8) {
+        int c = c0;
+        for (; c + 8 <= c1; c += 8) {
+            int32_t tmp[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) tmp[u] = chunk_cnt[(size_t)(c + u) * e_count + e];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) sum += tmp[u];
+        }
+        for (; c < c1; ++c) sum += chunk_cnt[(size_t)c * e_count + e];
+    }
+    s_grp[tid] = sum;
+    __syncthreads();
+    int32_t run = 0, total = 0;
+    for (int j = 0; j < G; ++j) {
+        const int32_t v = s_grp[j * e_pad + e];
+        if (j < g) run += v;
+        total += v;
+    }
+    if (e < e_count) {
+        int c = c0;
+        for (; c + 8 <= c1; c += 8) {
             int32_t tmp[8];
 #pragma unroll
             for (int u = 0; u < 8; ++u) tmp[u] = chunk_cnt[(size_t)(c + u) * e_count + e];
@@ -118,30 +147,32 @@ scan_kernel(int32_t* __restrict__ chunk_cnt, int n_chunks, int e_count,
                 run += tmp[u];
             }
         }
-        for (; c < n_chunks; ++c) {
+        for (; c < c1; ++c) {
             const int32_t tmp = chunk_cnt[(size_t)c * e_count + e];
             chunk_cnt[(size_t)c * e_count + e] = run;
             run += tmp;
         }
-        counts[e] = run;
+        if (g == 0) counts[e] = total;
     }
-    s_tot[e] = (e < e_count) ? run : 0;
+    __syncthreads();
+    s_tot[tid] = (g == 0 && e < e_count) ? total : 0;   // g == 0: tid == e
     __syncthreads();
     // inclusive Hillis-Steele scan over 1024 entries
     for (int off = 1; off < kMaxExperts; off <<= 1) {
-        const int32_t add = (e >= off) ? s_tot[e - off] : 0;
+        const int32_t add = (tid >= off) ? s_tot[tid - off] : 0;
         __syncthreads();
-        s_tot[e] += add;
+        s_tot[tid] += add;
         __syncthreads();
     }
-    if (e < e_count) offsets[e + 1] = s_tot[e];
-    if (e == 0) offsets[0] = 0;
+    if (tid < e_count) offsets[tid + 1] = s_tot[tid];
+    if (tid == 0) offsets[0] = 0;
 }
 
 // ------------------------------------------------------------ stable positions
 // Each wave walks its chunk 64 slots at a time.  cur[e] = next free row of
 // expert e for this chunk; lanes that share an expert take consecutive rows in
-// lane order (= flat-slot order), found with a ballot per distinct expert.
+// lane order (= flat-slot order): the set of such lanes is the intersection of
+// the ballots of the expert id's bits, a lane's rank the set bits below it.
 __global__ void __launch_bounds__(kRouteThreads)
 position_kernel(const int32_t* __restrict__ topk_idx, int F, int e_start, int e_count,
                 const int32_t* __restrict__ chunk_base, const int32_t* __restrict__ offsets,
@@ -163,19 +194,19 @@ position_kernel(const int32_t* __restrict__ topk_idx, int F, int e_start, int e_
             el = topk_idx[f] - e_start;
             if (el < 0 || el >= e_count) el = -1;
         }
-        int row = -1;
-        uint64_t remaining = __ballot(el >= 0);
-        while (remaining) {
-            const int leader = __builtin_ctzll(remaining);
-            const int e0 = __shfl(el, leader);
-            const uint64_t m = __ballot(el == e0);
-            const int base = cur[e0];
-            __builtin_amdgcn_wave_barrier();
-            if (el == e0) row = base + __popcll(m & lt_mask);
-            if (lane == leader) cur[e0] = base + __popcll(m);
-            __builtin_amdgcn_wave_barrier();
-            remaining &= ~m;
+        // lanes with the same expert: intersect the ballots of the expert id's bits
+        uint64_t m = __ballot(el >= 0);
+        for (int b = 0; (1 << b) < e_count; ++b) {
+            const uint64_t bb = __ballot((el >> b) & 1);
+            m &= ((el >> b) & 1) ? bb : ~bb;
         }
+        int row = -1;
+        if (el >= 0) {
+            row = cur[el] + __popcll(m & lt_mask);
+        }
+        __builtin_amdgcn_wave_barrier();
+        if (el >= 0 && (m >> lane) <= 1ull) cur[el] = row + 1;   // the group's last lane moves the cursor
+        __builtin_amdgcn_wave_barrier();
         if (f < F) {
             inv_perm[f] = row;
             if (row >= 0) perm[row] = f;
