@@ -178,13 +178,25 @@ __device__ __forceinline__ int queue_lag(int total_producer_tasks, int ec) {
 // Bounded wait for *p >= need.  Returns false (and raises the status word) if
 // the bound is exceeded or another worker already raised it, so that every
 // wave leaves the kernel in finite time whatever happens.
+__device__ __forceinline__ void fence_acquire() {
+#ifndef UNIEP_NO_ACQUIRE
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+#endif
+}
+// The polls are relaxed loads; the one acquire fence follows the successful
+// poll.  An acquire per poll would invalidate this XCD's L2 at the polling
+// rate and slow down every tile still running on it.
 __device__ __forceinline__ bool wait_ge(const int* p, int need, int* ctrl, long long limit_ticks,
                                         int stat_word = CTRL_WAIT_TICKS) {
-    if (ld_acquire(p) >= need) return true;
+    if (ld_relaxed(p) >= need) {
+        fence_acquire();
+        return true;
+    }
     const long long t0 = wall_clock64();
     for (;;) {
-        __builtin_amdgcn_s_sleep(8);
-        if (ld_acquire(p) >= need) {
+        __builtin_amdgcn_s_sleep(16);
+        if (ld_relaxed(p) >= need) {
+            fence_acquire();
             atomicAdd(ctrl + stat_word, (int)(wall_clock64() - t0));
             return true;
         }

@@ -26,7 +26,14 @@ enum TaskType { TASK_GEMM1 = 0, TASK_GEMM2 = 1, TASK_COMBINE = 2 };
 __device__ unsigned long long g_prof[3][8];
 #define PROF_NOW() wall_clock64()
 #define PROF_ADD(type, slot, val) do { if (threadIdx.x == 0) atomicAdd(&g_prof[type][slot], (unsigned long long)(val)); } while (0)
+// per-worker event trace: [worker][event] = {type, start tick, end tick, xcd}
+constexpr int kTraceEvents = 96;
+__device__ long long g_trace[512][kTraceEvents][4];
+#define TRACE_EVENT(n, type, t0) do { if (threadIdx.x == 0 && blockIdx.x < 512 && (n) < kTraceEvents) { \
+    g_trace[blockIdx.x][n][0] = (type); g_trace[blockIdx.x][n][1] = (t0); g_trace[blockIdx.x][n][2] = wall_clock64(); \
+    g_trace[blockIdx.x][n][3] = home; } ++(n); } while (0)
 #else
+#define TRACE_EVENT(n, type, t0) do { } while (0)
 #define PROF_NOW() 0ll
 #define PROF_ADD(type, slot, val) do { } while (0)
 #endif
@@ -343,9 +350,13 @@ fwd_worker_kernel(FwdParams p, int phase) {
     unsigned exhausted = 0;
     if (threadIdx.x == 0) s_task = fetch_task(ctrl, pass, home, exhausted, use_lists, use_tail);
     __syncthreads();
+    int n_ev = 0;
+    (void)n_ev;
     for (;;) {
         const int id = s_task;
         if (id == kFetchDone) break;
+        const long long t_ev = PROF_NOW();
+        (void)t_ev;
         PendingFetch pf;
         pf.q = -1;
         pf.id = 0;
@@ -360,12 +371,14 @@ fwd_worker_kernel(FwdParams p, int phase) {
                 gemm1_task<NW>(p, rt, ct, smem);
                 __syncthreads();   // all h stores of the tile are complete at workgroup scope
                 if (threadIdx.x == 0) add_release(p.flag1 + task.rt, 1);
+                TRACE_EVENT(n_ev, TASK_GEMM1 + 16 * rt.rows, t_ev);
             } else {
                 if (threadIdx.x == 0) s_ok = wait_ge(p.flag1 + task.rt, p.nct1, ctrl, p.spin_ticks);
                 __syncthreads();
                 if (s_ok) {
                     const RowTile rt = p.rt[task.rt];
                     gemm2_task<NW>(p, rt, ct, smem);
+                    TRACE_EVENT(n_ev, TASK_GEMM2 + 16 * rt.rows, t_ev);
                 }
             }
         } else {
@@ -377,7 +390,9 @@ fwd_worker_kernel(FwdParams p, int phase) {
             if (threadIdx.x == 0)
                 s_ok = wait_ge(ctrl + CTRL_DONE, ctrl[CTRL_NWAIT], ctrl, p.spin_ticks, CTRL_TAIL_WAIT_TICKS);
             __syncthreads();
+            TRACE_EVENT(n_ev, 3, t_ev);   // wait before a tail task
             if (s_ok) combine_task<NW>(p, -1 - id);
+            TRACE_EVENT(n_ev, TASK_COMBINE, t_ev);
         }
         __syncthreads();   // every thread has read s_task / s_ok of this round
         if (threadIdx.x == 0) s_task = fetch_finish(pf, ctrl, pass, home, exhausted, use_lists, use_tail);
@@ -496,6 +511,10 @@ int fwd_launch(const moe_shape_t& s, const void* x, const void* w_gate, const vo
 #ifdef UNIEP_PROFILE
 extern "C" int moe_debug_prof(unsigned long long* out, int reset) {
     if (hipDeviceSynchronize() != hipSuccess) return MOE_ERR_HIP;
+    if (reset == 2) {   // out receives the event trace of the last launch instead
+        return hipMemcpyFromSymbol(out, HIP_SYMBOL(g_trace), sizeof(long long) * 512 * kTraceEvents * 4) ==
+                       hipSuccess ? MOE_OK : MOE_ERR_HIP;
+    }
     if (hipMemcpyFromSymbol(out, HIP_SYMBOL(g_prof), sizeof(unsigned long long) * 24) != hipSuccess)
         return MOE_ERR_HIP;
     if (reset) {
