@@ -218,8 +218,9 @@ __device__ __forceinline__ void dh_task(const BwdParams& p, const RowTile rt, in
                     dgp[q] = pack_bf16x2(dg[2 * q], dg[2 * q + 1]);
                     dup[q] = pack_bf16x2(du[2 * q], du[2 * q + 1]);
                 }
-                *(u32x4_t*)(p.dgu + base) = dgp;
-                *(u32x4_t*)(p.dgu + base + (size_t)I * 2) = dup;
+                // consumed by dXp / dW_gate / dW_up tiles on any XCD
+                store_wt16(p.dgu + base, dgp);
+                store_wt16(p.dgu + base + (size_t)I * 2, dup);
             }
         }
     }
@@ -448,10 +449,11 @@ bwd_worker_kernel(BwdParams p, int phase) {
             } else if (type == B_DH) {
                 const RowTile rt = p.rt[task.rt];
                 dh_task<NW>(p, rt, ct, smem);
-                __syncthreads();
+                wait_stores();
+                __syncthreads();   // the write-through dG|dU stores of every wave have completed
                 if (threadIdx.x == 0) {
-                    add_release(p.flag_rt + task.rt, 1);
-                    add_release(p.flag_e + rt.expert, 1);
+                    add_relaxed(p.flag_rt + task.rt, 1);
+                    add_relaxed(p.flag_e + rt.expert, 1);
                 }
             } else if (type == B_DWD) {
                 dwd_task<NW>(p, task.rt / p.mt_dwd, task.rt % p.mt_dwd, ct, smem);

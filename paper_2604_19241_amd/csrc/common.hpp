@@ -46,6 +46,24 @@ __device__ __forceinline__ void add_release(int* p, int v) {
 #endif
 }
 
+// Write-through stores (agent scope): the data goes past this XCD's L2 to the
+// memory side, so a consumer on any XCD sees it once the store has completed
+// (s_waitcnt vmcnt(0)) and the consumer has acquired.  Producers that publish a
+// tile written only with these stores can signal with a relaxed atomic instead
+// of a release, which would write back the whole L2 of the XCD.
+__device__ __forceinline__ void store_wt8(void* p, u32x2_t v) {
+    __hip_atomic_store((uint64_t*)p, __builtin_bit_cast(uint64_t, v), __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void store_wt16(void* p, u32x4_t v) {
+    asm volatile("global_store_dwordx4 %0, %1, off sc1" : : "v"(p), "v"(v) : "memory");
+}
+// All write-through stores of this wave have completed.
+__device__ __forceinline__ void wait_stores() { asm volatile("s_waitcnt vmcnt(0)" : : : "memory"); }
+__device__ __forceinline__ void add_relaxed(int* p, int v) {
+    __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 // ---- work queues -----------------------------------------------------------
 // The GEMM tasks are cut into kQueues lists, one per XCD (each XCD has its own
 // L2): expert e goes to list e % kQueues, so the tiles that share an expert's

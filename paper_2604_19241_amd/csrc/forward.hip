@@ -224,7 +224,7 @@ __device__ __forceinline__ void gemm1_task(const FwdParams& p, const RowTile rt,
         if (m < rt.rows && col_ok) {
             const size_t row = (size_t)(rt.row0 + m);
             u32x2_t hp = {pack_bf16x2(hv[0], hv[1]), pack_bf16x2(hv[2], hv[3])};
-            *(u32x2_t*)(p.h + (row * I + hcol) * 2) = hp;
+            store_wt8(p.h + (row * I + hcol) * 2, hp);   // consumed by GEMM2 tiles on any XCD
             if (p.gu) *(u32x4_t*)(p.gu + (row * 2 * I + (odd ? I : 0) + gcol) * 2) = pack_row8(acc, v);
         }
     }
@@ -369,8 +369,9 @@ fwd_worker_kernel(FwdParams p, int phase) {
             } else if (type == TASK_GEMM1) {
                 const RowTile rt = p.rt[task.rt];
                 gemm1_task<NW>(p, rt, ct, smem);
-                __syncthreads();   // all h stores of the tile are complete at workgroup scope
-                if (threadIdx.x == 0) add_release(p.flag1 + task.rt, 1);
+                wait_stores();
+                __syncthreads();   // the write-through h stores of every wave have completed
+                if (threadIdx.x == 0) add_relaxed(p.flag1 + task.rt, 1);
                 TRACE_EVENT(n_ev, TASK_GEMM1 + 16 * rt.rows, t_ev);
             } else {
                 if (threadIdx.x == 0) s_ok = wait_ge(p.flag1 + task.rt, p.nct1, ctrl, p.spin_ticks);
