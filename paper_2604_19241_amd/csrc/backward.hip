@@ -258,7 +258,7 @@ __device__ __forceinline__ void dxp_task(const BwdParams& p, const RowTile rt, i
         for (int v = 0; v < 16; ++v) {
             const int m = wave * 32 + frag_row(v, lane);
             if (m < rt.rows)
-                *(u32x4_t*)(p.dxp + ((size_t)(rt.row0 + m) * d + col) * 2) = pack_row8(acc, v);
+                store_stream16(p.dxp + ((size_t)(rt.row0 + m) * d + col) * 2, pack_row8(acc, v));
         }
     }
 }
@@ -295,7 +295,7 @@ __device__ __forceinline__ void dwd_task(const BwdParams& p, int e, int mt, int 
         for (int v = 0; v < 16; ++v) {
             const int m = mt * G::BM + tr_tile_row<NW>(wave * 32 + frag_row(v, lane));
             if (m < I)
-                *(u32x4_t*)(p.dw_down + (((size_t)e * I + m) * d + col) * 2) = pack_row8(acc, v);
+                store_stream16(p.dw_down + (((size_t)e * I + m) * d + col) * 2, pack_row8(acc, v));
         }
     }
 }
@@ -338,7 +338,7 @@ __device__ __forceinline__ void dwgu_task(const BwdParams& p, int e, int mt, int
         for (int v = 0; v < 16; ++v) {
             const int m = mt * G::BM + tr_tile_row<NW>(wave * 32 + frag_row(v, lane));
             if (m < d)
-                *(u32x4_t*)(dst + (((size_t)e * d + m) * I + icol) * 2) = pack_row8(acc, v);
+                store_stream16(dst + (((size_t)e * d + m) * I + icol) * 2, pack_row8(acc, v));
         }
     }
 }
@@ -400,7 +400,7 @@ __device__ __forceinline__ void dx_task(const BwdParams& p, int block) {
             u32x4_t out;
 #pragma unroll
             for (int q = 0; q < 4; ++q) out[q] = pack_bf16x2(a[2 * q], a[2 * q + 1]);
-            *(u32x4_t*)(p.dx + ((size_t)t * d + c) * 2) = out;
+            store_stream16(p.dx + ((size_t)t * d + c) * 2, out);
         }
         if (want_dots) {
 #pragma unroll

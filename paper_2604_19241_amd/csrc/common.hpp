@@ -55,8 +55,20 @@ __device__ __forceinline__ void store_wt8(void* p, u32x2_t v) {
     __hip_atomic_store((uint64_t*)p, __builtin_bit_cast(uint64_t, v), __ATOMIC_RELAXED,
                        __HIP_MEMORY_SCOPE_AGENT);
 }
+// (two 8-byte stores: the compiler has no 16-byte atomic store, and a store hidden in inline
+// assembly would escape its hazard handling for the data registers)
 __device__ __forceinline__ void store_wt16(void* p, u32x4_t v) {
-    asm volatile("global_store_dwordx4 %0, %1, off sc1" : : "v"(p), "v"(v) : "memory");
+    store_wt8(p, u32x2_t{v[0], v[1]});
+    store_wt8((char*)p + 8, u32x2_t{v[2], v[3]});
+}
+// Streaming store for outputs that are written once and not read again soon
+// (o, the G|U stash, dXp, dW, y, dX): they should not displace operands in L2.
+__device__ __forceinline__ void store_stream16(void* p, u32x4_t v) {
+#ifdef UNIEP_X_NOSTREAM
+    *(u32x4_t*)p = v;
+#else
+    __builtin_nontemporal_store(v, (u32x4_t*)p);
+#endif
 }
 // All write-through stores of this wave have completed.
 __device__ __forceinline__ void wait_stores() { asm volatile("s_waitcnt vmcnt(0)" : : : "memory"); }
@@ -183,14 +195,15 @@ __device__ __forceinline__ void queue_positions(const int* ga, const int* gb, in
 }
 
 // Lag (in experts) between an expert's producer and consumer blocks: enough
-// producer tasks in between that a workgroup which runs ahead finds other
-// producers to do instead of waiting (about 1.5 x the workgroups of one XCD).
+// producer tasks in between (about four rounds of one XCD's workgroups) that a
+// consumer's inputs are complete when it is fetched, also near the end of the
+// lists, where stealing workgroups drain the consumer blocks quickly.
 __device__ __forceinline__ int queue_lag(int total_producer_tasks, int ec) {
 #ifdef UNIEP_X_LAG
     return UNIEP_X_LAG;
 #endif
     const int per = max(1, total_producer_tasks / max(1, ec));
-    return min(8, max(1, (48 + per - 1) / per));
+    return min(16, max(1, (128 + per - 1) / per));
 }
 
 // Bounded wait for *p >= need.  Returns false (and raises the status word) if

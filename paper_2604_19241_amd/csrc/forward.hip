@@ -201,6 +201,8 @@ __device__ __forceinline__ void gemm1_task(const FwdParams& p, const RowTile rt,
 #endif
     PROF_ADD(TASK_GEMM1, 2, PROF_NOW() - t_start);
     PROF_ADD(TASK_GEMM1, 5, d / BK);
+    const long long t_main = PROF_NOW();
+    (void)t_main;
 
     // epilogue: SwiGLU on the accumulators; lanes (2q, 2q+1) trade halves so that
     // each ends with G and U of 4 consecutive h-columns.
@@ -225,9 +227,16 @@ __device__ __forceinline__ void gemm1_task(const FwdParams& p, const RowTile rt,
             const size_t row = (size_t)(rt.row0 + m);
             u32x2_t hp = {pack_bf16x2(hv[0], hv[1]), pack_bf16x2(hv[2], hv[3])};
             store_wt8(p.h + (row * I + hcol) * 2, hp);   // consumed by GEMM2 tiles on any XCD
-            if (p.gu) *(u32x4_t*)(p.gu + (row * 2 * I + (odd ? I : 0) + gcol) * 2) = pack_row8(acc, v);
+            if (p.gu) store_stream16(p.gu + (row * 2 * I + (odd ? I : 0) + gcol) * 2, pack_row8(acc, v));
         }
     }
+#ifdef UNIEP_PROFILE
+    if (rt.rows == G::BM) {
+        PROF_ADD(TASK_GEMM1, 0, 1);
+        PROF_ADD(TASK_GEMM1, 1, t_main - t_start);
+        PROF_ADD(TASK_GEMM1, 3, PROF_NOW() - t_main);
+    }
+#endif
 }
 
 // ------------------------------------------------------------- GEMM2 task
@@ -263,7 +272,7 @@ __device__ __forceinline__ void gemm2_task(const FwdParams& p, const RowTile rt,
         for (int v = 0; v < 16; ++v) {
             const int m = wave * 32 + frag_row(v, lane);
             if (m < rt.rows)
-                *(u32x4_t*)(p.o + ((size_t)(rt.row0 + m) * d + col) * 2) = pack_row8(acc, v);
+                store_stream16(p.o + ((size_t)(rt.row0 + m) * d + col) * 2, pack_row8(acc, v));
         }
     }
 }
@@ -322,8 +331,8 @@ __device__ __forceinline__ void combine_task(const FwdParams& p, int block) {
                 y0[q] = pack_bf16x2(a0[2 * q], a0[2 * q + 1]);
                 y1[q] = pack_bf16x2(a1[2 * q], a1[2 * q + 1]);
             }
-            *(u32x4_t*)(p.y + ((size_t)t * d + c0) * 2) = y0;
-            if (two) *(u32x4_t*)(p.y + ((size_t)t * d + c1) * 2) = y1;
+            store_stream16(p.y + ((size_t)t * d + c0) * 2, y0);
+            if (two) store_stream16(p.y + ((size_t)t * d + c1) * 2, y1);
         }
     }
 }
@@ -368,10 +377,17 @@ fwd_worker_kernel(FwdParams p, int phase) {
                 // staged launch: another phase's task, nothing to do
             } else if (type == TASK_GEMM1) {
                 const RowTile rt = p.rt[task.rt];
+#ifdef UNIEP_PROFILE
+                if (rt.rows == Geom<NW>::BM) PROF_ADD(TASK_GEMM1, 4, PROF_NOW() - t_ev);
+                const long long t_g1 = PROF_NOW();
+#endif
                 gemm1_task<NW>(p, rt, ct, smem);
                 wait_stores();
                 __syncthreads();   // the write-through h stores of every wave have completed
                 if (threadIdx.x == 0) add_relaxed(p.flag1 + task.rt, 1);
+#ifdef UNIEP_PROFILE
+                if (rt.rows == Geom<NW>::BM) PROF_ADD(TASK_GEMM1, 6, PROF_NOW() - t_g1);
+#endif
                 TRACE_EVENT(n_ev, TASK_GEMM1 + 16 * rt.rows, t_ev);
             } else {
                 if (threadIdx.x == 0) s_ok = wait_ge(p.flag1 + task.rt, p.nct1, ctrl, p.spin_ticks);

@@ -536,6 +536,7 @@ __device__ __forceinline__ float dpp_swap_pair(float x) {   // value of lane ^ 1
     return __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(x), 0xB1, 0xF, 0xF, true));
 }
 
-__device__ __forceinline__ float sigmoid_f(float z) { return __frcp_rn(1.f + __expf(-z)); }
+// v_exp_f32 and v_rcp_f32 (1 ulp each): far inside the bf16 rounding of the results
+__device__ __forceinline__ float sigmoid_f(float z) { return __builtin_amdgcn_rcpf(1.f + __expf(-z)); }
 
 }  // namespace uniep
