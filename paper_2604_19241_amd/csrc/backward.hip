@@ -88,6 +88,7 @@ __global__ void __launch_bounds__(1024) bwd_prologue_kernel(BwdParams p) {
     __shared__ int32_t s_qbase[kQueues + 1];
     __shared__ int32_t s_qlen[kQueues];
     __shared__ int32_t s_lag;
+    __shared__ ListPlan s_plan;
     const int e = threadIdx.x;
     const int ec = p.s.e_count;
     const int per_dwd = p.mt_dwd * p.nt_dwd, per_dwgu = p.mt_dwgu * p.nt_dwgu;
@@ -96,6 +97,7 @@ __global__ void __launch_bounds__(1024) bwd_prologue_kernel(BwdParams p) {
         cnt = p.offsets[e + 1] - p.offsets[e];
         nt = (cnt + BM - 1) / BM;
     }
+    s_plan.cost[e] = cnt;
     s_scan[e] = nt;
     s_ga[e] = (e < ec) ? nt * p.nct_dh + per_dwd : 0;
     s_gb[e] = (e < ec) ? nt * p.nct_dxp + per_dwgu : 0;
@@ -107,9 +109,13 @@ __global__ void __launch_bounds__(1024) bwd_prologue_kernel(BwdParams p) {
         __syncthreads();
     }
     const int nrt = s_scan[kMaxExperts - 1];
+    plan_lists(s_plan, ec);
     if (e < kQueues) {   // length of list e
         int len = 0;
-        for (int j = e; j < ec; j += kQueues) len += s_ga[j] + s_gb[j];
+        for (int j = 0; j < s_plan.size[e]; ++j) {
+            const int x = s_plan.member[e][j];
+            len += s_ga[x] + s_gb[x];
+        }
         s_qlen[e] = len;
     }
     __syncthreads();
@@ -138,10 +144,10 @@ __global__ void __launch_bounds__(1024) bwd_prologue_kernel(BwdParams p) {
         p.flag_e[e] = 0;
         p.need_e[e] = nt * p.nct_dh;
         int pa, pb;
-        queue_positions(s_ga, s_gb, e, ec, s_lag, pa, pb);
+        queue_positions(s_plan, s_ga, s_gb, e, s_lag, pa, pb);
         s_rt0[e] = rt0;
-        s_ta[e] = s_qbase[e & (kQueues - 1)] + pa;
-        s_tb[e] = s_qbase[e & (kQueues - 1)] + pb;
+        s_ta[e] = s_qbase[s_plan.list_of[e]] + pa;
+        s_tb[e] = s_qbase[s_plan.list_of[e]] + pb;
     }
     __syncthreads();
     for (int x = e >> 6; x < ec; x += 16) {   // one wave writes the two blocks of an expert

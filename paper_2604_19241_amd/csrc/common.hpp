@@ -78,12 +78,11 @@ __device__ __forceinline__ void add_relaxed(int* p, int v) {
 
 // ---- work queues -----------------------------------------------------------
 // The GEMM tasks are cut into kQueues lists, one per XCD (each XCD has its own
-// L2): expert e goes to list e % kQueues, so the tiles that share an expert's
-// weights and rows run on one XCD and meet in its L2, and an expert's consumer
-// tiles (GEMM2 / dXp, dW_gate, dW_up) find the producer's output in that L2.
-// Inside a list the experts are pipelined with a lag of one: producer block of
-// expert i+1 comes before the consumer block of expert i, so consumers rarely
-// wait.  A workgroup drains its own XCD's list first and then steals from the
+// L2): every expert belongs to one list (see ListPlan), so the tiles that share
+// an expert's weights and rows run on one XCD and meet in its L2.  Inside a list
+// the experts are pipelined with a lag: the producer block of the list's
+// (i+L)-th expert comes before the consumer block of its i-th, so consumers
+// rarely wait.  A workgroup drains its own XCD's list first and then steals from the
 // others; the token-parallel tail tasks (combine / dX) come last.  Dependencies
 // point to earlier entries of the same list, and an entry is fetched only by a
 // running workgroup, so the lowest unfinished entry of every list can always run.
@@ -170,19 +169,68 @@ __device__ __forceinline__ int fetch_finish(const PendingFetch f, int* ctrl, int
     return fetch_task(ctrl, pass, home, exhausted, use_lists, use_tail);
 }
 
+// Which expert goes to which list.  The lists should end at the same time:
+// work that one XCD steals from another list has lost the L2 sharing between
+// the tiles of a row tile and of an expert, and runs about half as fast.  So the
+// experts are sorted by cost (rows, descending; ties by id) and dealt to the
+// lists in boustrophedon order (ranks 0..7 to lists 0..7, ranks 8..15 to lists
+// 7..0, ...).  Big experts come first in every list, small ones fill the end.
+// The plan depends only on the counts, so it is the same on every run.
+struct ListPlan {
+    int32_t cost[kMaxExperts];              // in: cost of every local expert (0 beyond e_count)
+    uint16_t order[kMaxExperts];            // experts by descending cost
+    uint16_t member[kQueues][kMaxExperts];  // member[q][i] = i-th expert of list q
+    uint16_t list_of[kMaxExperts];
+    uint16_t slot_of[kMaxExperts];
+    int32_t size[kQueues];                  // experts per list
+};
+
+// Called by all 1024 threads of the prologue workgroup after plan.cost is written
+// (and a barrier).  Ends with a barrier.
+__device__ __forceinline__ void plan_lists(ListPlan& plan, int ec) {
+    const int e = threadIdx.x;
+    if (e < ec) {
+        const int32_t mine = plan.cost[e];
+        int r = 0;
+        for (int j = 0; j < ec; ++j) {
+            const int32_t c = plan.cost[j];
+            r += (c > mine || (c == mine && j < e)) ? 1 : 0;
+        }
+        plan.order[r] = (uint16_t)e;
+    }
+    __syncthreads();
+    if (e < ec) {
+        const int x = plan.order[e];
+        const int i = e / kQueues, c = e % kQueues;
+        const int q = (i & 1) ? kQueues - 1 - c : c;
+        plan.member[q][i] = (uint16_t)x;
+        plan.list_of[x] = (uint16_t)q;
+        plan.slot_of[x] = (uint16_t)i;
+    }
+    if (e < kQueues) {
+        int n = 0;
+        for (int i = 0; i * kQueues < ec; ++i) {
+            const int c = (i & 1) ? kQueues - 1 - e : e;
+            n += (i * kQueues + c < ec) ? 1 : 0;
+        }
+        plan.size[e] = n;
+    }
+    __syncthreads();
+}
+
 // Position of expert e's producer block (pos_a) and consumer block (pos_b)
 // inside its list, given the block sizes ga[], gb[] of all experts (shared
-// memory) and the lag L >= 1: the consumer block of expert i follows the
-// producer block of expert i+L.  List order for L = 1:
+// memory) and the lag L >= 1: the consumer block of the list's i-th expert
+// follows the producer block of its (i+L)-th.  List order for L = 1:
 // A0, A1, B0, A2, B1, ..., A(n-1), B(n-2), B(n-1).
-__device__ __forceinline__ void queue_positions(const int* ga, const int* gb, int e, int ec, int lag,
-                                                int& pos_a, int& pos_b) {
-    const int q = e & (kQueues - 1), i = e / kQueues;
-    const int nq = (ec - q + kQueues - 1) / kQueues;
+__device__ __forceinline__ void queue_positions(const ListPlan& plan, const int* ga, const int* gb, int e,
+                                                int lag, int& pos_a, int& pos_b) {
+    const int q = plan.list_of[e], i = plan.slot_of[e];
+    const int nq = plan.size[q];
     int sa_i = 0, sb_i = 0, sb_lag = 0, sa_n = 0;
     const int lim = min(i + lag + 1, nq);
     for (int j = 0; j < lim; ++j) {
-        const int ej = q + kQueues * j;
+        const int ej = plan.member[q][j];
         if (j < i) {
             sa_i += ga[ej];
             sb_i += gb[ej];
@@ -224,8 +272,12 @@ __device__ __forceinline__ bool wait_ge(const int* p, int need, int* ctrl, long 
         return true;
     }
     const long long t0 = wall_clock64();
-    for (;;) {
-        __builtin_amdgcn_s_sleep(16);
+    // Back off to one poll per ~3 us: a few hundred waiting workgroups polling one address at full
+    // rate saturate its memory channel and slow down the tiles that are still running.
+    for (int round = 0;; ++round) {
+        if (round < 4) __builtin_amdgcn_s_sleep(16);
+        else if (round < 8) __builtin_amdgcn_s_sleep(48);
+        else __builtin_amdgcn_s_sleep(127);
         if (ld_relaxed(p) >= need) {
             fence_acquire();
             atomicAdd(ctrl + stat_word, (int)(wall_clock64() - t0));

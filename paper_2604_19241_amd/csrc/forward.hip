@@ -31,7 +31,8 @@ constexpr int kTraceEvents = 96;
 __device__ long long g_trace[512][kTraceEvents][4];
 #define TRACE_EVENT(n, type, t0) do { if (threadIdx.x == 0 && blockIdx.x < 512 && (n) < kTraceEvents) { \
     g_trace[blockIdx.x][n][0] = (type); g_trace[blockIdx.x][n][1] = (t0); g_trace[blockIdx.x][n][2] = wall_clock64(); \
-    g_trace[blockIdx.x][n][3] = home; } ++(n); } while (0)
+    int lq_ = 0; for (int q_ = 1; q_ < kQueues; ++q_) if (id >= ctrl[CTRL_QBASE + q_]) lq_ = q_; \
+    g_trace[blockIdx.x][n][3] = home + 16 * lq_; } ++(n); } while (0)
 #else
 #define TRACE_EVENT(n, type, t0) do { } while (0)
 #define PROF_NOW() 0ll
@@ -75,6 +76,7 @@ __global__ void __launch_bounds__(1024) fwd_prologue_kernel(FwdParams p) {
     __shared__ int32_t s_qbase[kQueues + 1];
     __shared__ int32_t s_qlen[kQueues];
     __shared__ int32_t s_lag;
+    __shared__ ListPlan s_plan;
     const int e = threadIdx.x;
     const int ec = p.s.e_count;
     int cnt = 0, nt = 0;
@@ -82,6 +84,7 @@ __global__ void __launch_bounds__(1024) fwd_prologue_kernel(FwdParams p) {
         cnt = p.offsets[e + 1] - p.offsets[e];
         nt = (cnt + BM - 1) / BM;
     }
+    s_plan.cost[e] = cnt;
     s_scan[e] = nt;
     s_g1[e] = nt * p.nct1;
     s_g2[e] = nt * p.nct2;
@@ -93,9 +96,13 @@ __global__ void __launch_bounds__(1024) fwd_prologue_kernel(FwdParams p) {
         __syncthreads();
     }
     const int nrt = s_scan[kMaxExperts - 1];
+    plan_lists(s_plan, ec);
     if (e < kQueues) {   // length of list e
         int len = 0;
-        for (int j = e; j < ec; j += kQueues) len += s_g1[j] + s_g2[j];
+        for (int j = 0; j < s_plan.size[e]; ++j) {
+            const int x = s_plan.member[e][j];
+            len += s_g1[x] + s_g2[x];
+        }
         s_qlen[e] = len;
     }
     __syncthreads();
@@ -125,10 +132,10 @@ __global__ void __launch_bounds__(1024) fwd_prologue_kernel(FwdParams p) {
             p.flag1[rt0 + i] = 0;
         }
         int pos1, pos2;
-        queue_positions(s_g1, s_g2, e, ec, s_lag, pos1, pos2);
+        queue_positions(s_plan, s_g1, s_g2, e, s_lag, pos1, pos2);
         s_rt0[e] = rt0;
-        s_t1[e] = s_qbase[e & (kQueues - 1)] + pos1;
-        s_t2[e] = s_qbase[e & (kQueues - 1)] + pos2;
+        s_t1[e] = s_qbase[s_plan.list_of[e]] + pos1;
+        s_t2[e] = s_qbase[s_plan.list_of[e]] + pos2;
     }
     __syncthreads();
     for (int x = e >> 6; x < ec; x += 16) {   // one wave writes the two blocks of an expert
