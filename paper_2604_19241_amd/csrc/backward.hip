@@ -438,7 +438,10 @@ bwd_worker_kernel(BwdParams p, int phase) {
     const bool publishes = phase < 0 || phase == B_DXP;
     bool arrived = false;
     unsigned exhausted = 0;
-    if (threadIdx.x == 0) s_task = fetch_task(ctrl, pass, home, exhausted, use_lists, use_tail);
+    if (threadIdx.x == 0) {
+        if (phase < 0) worker_started(ctrl, home);
+        s_task = fetch_task(ctrl, pass, home, exhausted, use_lists, use_tail);
+    }
     __syncthreads();
     for (;;) {
         const int id = s_task;
@@ -479,8 +482,12 @@ bwd_worker_kernel(BwdParams p, int phase) {
         } else {
             if (publishes && !arrived) {
                 arrived = true;
+                wait_stores();
                 __syncthreads();
-                if (threadIdx.x == 0) add_release(ctrl + CTRL_DONE, 1);
+                if (threadIdx.x == 0) {
+                    if (phase < 0) worker_arrived(ctrl, home, ctrl[CTRL_NWAIT], p.spin_ticks);
+                    else add_release(ctrl + CTRL_DONE, 1);
+                }
             }
             if (threadIdx.x == 0)
                 s_ok = wait_ge(ctrl + CTRL_DONE, ctrl[CTRL_NWAIT], ctrl, p.spin_ticks, CTRL_TAIL_WAIT_TICKS);
@@ -492,8 +499,12 @@ bwd_worker_kernel(BwdParams p, int phase) {
         __syncthreads();
     }
     if (publishes && !arrived) {
+        wait_stores();
         __syncthreads();
-        if (threadIdx.x == 0) add_release(ctrl + CTRL_DONE, 1);
+        if (threadIdx.x == 0) {
+            if (phase < 0) worker_arrived(ctrl, home, ctrl[CTRL_NWAIT], p.spin_ticks);
+            else add_release(ctrl + CTRL_DONE, 1);
+        }
     }
 }
 

@@ -101,7 +101,10 @@ enum CtrlWord {
     CTRL_QLEN = 8,     // [8]  entries per list
     CTRL_QBASE = 16,   // [8]  first entry of each list in the task array
     CTRL_CURSOR = 24,  // [kPasses][kQueues + 1]  list cursors and tail cursor per pass
-    CTRL_WORDS = 24 + kPasses * (kQueues + 1) + 2
+    CTRL_XCD_WORKERS = 24 + kPasses * (kQueues + 1) + 2,   // [8] workers that started on each XCD
+    CTRL_XCD_ARRIVED = CTRL_XCD_WORKERS + kQueues,         // [8] workers of each XCD that ran out of GEMM work
+    CTRL_STARTED = CTRL_XCD_ARRIVED + kQueues,             // workers that started
+    CTRL_WORDS = CTRL_STARTED + 1
 };
 
 constexpr int kFetchDone = INT32_MIN;
@@ -290,6 +293,27 @@ __device__ __forceinline__ bool wait_ge(const int* p, int need, int* ctrl, long 
             return false;
         }
     }
+}
+
+// Publication of the rows a persistent worker wrote with ordinary (write-back)
+// stores, for consumers that wait for ALL workers (the tail tasks).  A release
+// writes back the whole L2 of the XCD, which stalls the tiles still running on
+// it, so only the last worker of each XCD to run out of GEMM work releases, on
+// behalf of the XCD: the others only count themselves in after their own stores
+// have completed, which orders those stores before the releasing worker's
+// write-back.  worker_started() is called once at kernel start, worker_arrived()
+// once when the worker has no GEMM work left (both by one thread, the second
+// after s_waitcnt vmcnt(0) and a workgroup barrier).
+__device__ __forceinline__ void worker_started(int* ctrl, int xcd) {
+    add_relaxed(ctrl + CTRL_XCD_WORKERS + xcd, 1);
+    add_relaxed(ctrl + CTRL_STARTED, 1);
+}
+__device__ __forceinline__ void worker_arrived(int* ctrl, int xcd, int workers, long long limit_ticks) {
+    if (!wait_ge(ctrl + CTRL_STARTED, workers, ctrl, limit_ticks)) return;   // every worker is registered
+    const int on_xcd = ld_relaxed(ctrl + CTRL_XCD_WORKERS + xcd);
+    const int before = __hip_atomic_fetch_add(ctrl + CTRL_XCD_ARRIVED + xcd, 1, __ATOMIC_RELAXED,
+                                              __HIP_MEMORY_SCOPE_AGENT);
+    if (before + 1 == on_xcd) add_release(ctrl + CTRL_DONE, on_xcd);
 }
 
 struct RowTile {   // one row tile of one local expert

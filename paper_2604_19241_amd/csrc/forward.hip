@@ -364,7 +364,10 @@ fwd_worker_kernel(FwdParams p, int phase) {
     const bool publishes = phase < 0 || phase == TASK_GEMM2;
     bool arrived = false;
     unsigned exhausted = 0;
-    if (threadIdx.x == 0) s_task = fetch_task(ctrl, pass, home, exhausted, use_lists, use_tail);
+    if (threadIdx.x == 0) {
+        if (phase < 0) worker_started(ctrl, home);
+        s_task = fetch_task(ctrl, pass, home, exhausted, use_lists, use_tail);
+    }
     __syncthreads();
     int n_ev = 0;
     (void)n_ev;
@@ -408,8 +411,12 @@ fwd_worker_kernel(FwdParams p, int phase) {
         } else {
             if (publishes && !arrived) {   // first tail task: all of this worker's o rows are written
                 arrived = true;
+                wait_stores();
                 __syncthreads();
-                if (threadIdx.x == 0) add_release(ctrl + CTRL_DONE, 1);
+                if (threadIdx.x == 0) {
+                    if (phase < 0) worker_arrived(ctrl, home, ctrl[CTRL_NWAIT], p.spin_ticks);
+                    else add_release(ctrl + CTRL_DONE, 1);
+                }
             }
             if (threadIdx.x == 0)
                 s_ok = wait_ge(ctrl + CTRL_DONE, ctrl[CTRL_NWAIT], ctrl, p.spin_ticks, CTRL_TAIL_WAIT_TICKS);
@@ -423,8 +430,12 @@ fwd_worker_kernel(FwdParams p, int phase) {
         __syncthreads();
     }
     if (publishes && !arrived) {   // ran out of work without seeing a tail task
+        wait_stores();
         __syncthreads();
-        if (threadIdx.x == 0) add_release(ctrl + CTRL_DONE, 1);
+        if (threadIdx.x == 0) {
+            if (phase < 0) worker_arrived(ctrl, home, ctrl[CTRL_NWAIT], p.spin_ticks);
+            else add_release(ctrl + CTRL_DONE, 1);
+        }
     }
 }
 
