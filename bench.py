@@ -34,8 +34,9 @@ HBM_PEAK_GBS = 8000.0
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    # the shader clock needs some tens of milliseconds of load to ramp up: warm up for ~0.3 s
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--config", type=int, default=2, help="index into BASELINE.json configs")
     ap.add_argument("--schedule", type=int, default=0)
     ap.add_argument("--tile-rows", type=int, default=0)
@@ -49,13 +50,15 @@ def parse():
     return ap.parse_args()
 
 
-def event_ms(fn, n):
-    """Average milliseconds of fn() over n calls, HIP events on torch's current stream
-    (the stream the library launches on)."""
+def event_ms(fn, n, before=None):
+    """(average, median, min) milliseconds of fn() over n calls, HIP events on torch's current
+    stream (the stream the library launches on).  `before` runs untimed ahead of every call."""
     import torch
     evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
            for _ in range(n)]
     for a, b in evs:
+        if before is not None:
+            before()
         a.record()
         fn()
         b.record()
@@ -190,6 +193,18 @@ def main():
     ms_route = event_ms(route, n)
     ms_fwd = event_ms(fwd, n)
     ms_bwd = event_ms(bwd, n) if has_bwd else None
+    # the same with cold caches: a 512 MiB streaming copy ahead of every call evicts the weights,
+    # activations and routing tables from the L2s and the 256 MB Infinity Cache
+    flush_src = torch.zeros(512 << 20, dtype=torch.uint8, device="cuda")
+    flush_dst = torch.empty_like(flush_src)
+
+    def flush():
+        moe.moe_calibration_copy(flush_dst, flush_src)
+
+    nc = min(n, 30)
+    cold_fwd = event_ms(fwd, nc, before=flush)
+    cold_bwd = event_ms(bwd, nc, before=flush) if has_bwd else None
+    del flush_src, flush_dst
     fwd_tflops = f_fwd / (ms_fwd[0] * 1e-3) / 1e12
     # waves per workgroup the library picks (tile height 32 * nw): 8 from 160 rows per expert up
     nw = {128: 4, 256: 8}.get(args.tile_rows, 8 if cfg.T * cfg.k / cfg.E >= 160.0 else 4)
@@ -234,6 +249,9 @@ def main():
         "pct_of_bf16_mfma_peak": 100.0 * value / MFMA_BF16_PEAK_TFLOPS,
         "phases_ms": {"route": ms_route[0], "forward": ms_fwd[0],
                       "backward": ms_bwd[0] if ms_bwd else None},
+        "phases_ms_median_min": {"route": ms_route[1:], "forward": ms_fwd[1:],
+                                 "backward": ms_bwd[1:] if ms_bwd else None},
+        "phases_ms_cold_caches": {"forward": cold_fwd[0], "backward": cold_bwd[0] if cold_bwd else None},
         "forward_tflops": fwd_tflops,
         "backward_tflops": (f_bwd / (ms_bwd[0] * 1e-3) / 1e12) if ms_bwd else None,
         "expert_load": moe_synth.histogram_summary(counts),

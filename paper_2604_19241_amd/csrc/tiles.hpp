@@ -149,7 +149,8 @@ __device__ __forceinline__ void transpose_store(const u32x4_t (&in)[KR], char* d
 #ifdef UNIEP_X_NOTRANS   // timing experiments only (wrong results)
             o[p] = (j & 1) ? lo : hi;
 #else
-            o[p] = (j & 1) ? ((lo >> 16) | (hi & 0xffff0000u)) : ((lo & 0xffffu) | (hi << 16));
+            // one byte permute per word: {lo.hi16, hi.hi16} or {lo.lo16, hi.lo16}
+            o[p] = (j & 1) ? __builtin_amdgcn_perm(hi, lo, 0x07060302u) : __builtin_amdgcn_perm(hi, lo, 0x05040100u);
 #endif
         }
         char* d = dst + j * row_stride;
