@@ -91,6 +91,8 @@ __global__ void __launch_bounds__(256) calibration_copy_kernel(uniep::u32x4_t* _
         __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
 }
 
+__global__ void clear_status_kernel(int* ws) { ws[uniep::CTRL_STATUS] = 0; }
+
 extern "C" {
 
 int moe_calibration_copy(void* dst, const void* src, size_t bytes, void* stream) {
@@ -152,7 +154,10 @@ int moe_fused_forward(const moe_shape_t* shape, const void* x, const void* w_gat
         !aligned(w_down, 16) || !aligned(ws, 256) || !aligned(saved, 256))
         return MOE_ERR_ARG;
     if (ws_bytes < fwd_workspace_bytes(*shape)) return MOE_ERR_WORKSPACE;
-    if (shape->T == 0) return MOE_OK;
+    if (shape->T == 0) {   // nothing to compute: leave a clean status word for moe_device_status
+        hipLaunchKernelGGL(clear_status_kernel, dim3(1), dim3(1), 0, (hipStream_t)stream, (int*)ws);
+        return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
+    }
     char* wsb = (char*)ws;
     char *gu = nullptr, *h, *ob;
     if (saved) {

@@ -107,6 +107,16 @@ def test_null_and_misaligned_pointers_are_rejected_before_any_launch(lib):
     assert rc == b.MOE_ERR_ARG
 
 
+def test_calibration_copy_rejects_bad_arguments(lib):
+    from paper_2604_19241_amd import binding as b
+    lib.moe_calibration_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    assert lib.moe_calibration_copy(None, 256, 256, None) == b.MOE_ERR_ARG       # NULL destination
+    assert lib.moe_calibration_copy(256, None, 256, None) == b.MOE_ERR_ARG       # NULL source
+    assert lib.moe_calibration_copy(256, 264, 256, None) == b.MOE_ERR_ARG        # misaligned source
+    assert lib.moe_calibration_copy(256, 512, 100, None) == b.MOE_ERR_ARG        # size not a multiple of 16
+    assert lib.moe_calibration_copy(256, 512, 0, None) == b.MOE_OK               # nothing to copy, nothing launched
+
+
 def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
     from paper_2604_19241_amd import binding as b
     monkeypatch.setattr(b, "_lib", None)

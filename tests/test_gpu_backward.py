@@ -111,3 +111,40 @@ def test_backward_without_dtopk_w():
     assert g2["dtopk_w"] is None
     for key in KEYS:
         assert torch.equal(g1[key], g2[key])
+
+
+@pytest.mark.parametrize("tile_rows", [0, 256])
+def test_forward_backward_maximum_experts_and_topk(tile_rows):
+    """The shape limits at once: E = 1024 experts, k = 16 slots, most experts empty or with a
+    handful of rows; exercises the 1024-expert scan, sort and list planning of the prologues."""
+    cfg = moe_synth.small_config(T=130, d=128, E=1024, k=16, I=64)
+    check_backward(cfg, seed=21, schedule=1, tile_rows=tile_rows, wscale=4.0)
+
+
+def test_forward_backward_empty_batch():
+    """T = 0: nothing to route; y and dX are empty, every weight gradient is exactly zero."""
+    import paper_2604_19241_amd as moe
+    cfg = moe_synth.small_config(T=0, d=128, E=8, k=2, I=64)
+    shape = moe.make_shape(**cfg.shape_dict())
+    dev = {
+        "logits": torch.empty((0, cfg.E), dtype=torch.float32, device="cuda"),
+        "x": torch.empty((0, cfg.d), dtype=torch.bfloat16, device="cuda"),
+        "dy": torch.empty((0, cfg.d), dtype=torch.bfloat16, device="cuda"),
+        "w_gate": torch.randn((cfg.E, cfg.d, cfg.I), device="cuda").bfloat16(),
+        "w_up": torch.randn((cfg.E, cfg.d, cfg.I), device="cuda").bfloat16(),
+        "w_down": torch.randn((cfg.E, cfg.I, cfg.d), device="cuda").bfloat16(),
+    }
+    routing = moe.moe_route(shape, dev["logits"])
+    assert int(routing.offsets[-1]) == 0 and int(routing.counts.sum()) == 0
+    saved = moe.alloc_saved(shape, "cuda")
+    sizes = moe.moe_workspace_bytes(shape)
+    ws = torch.empty(sizes["fwd"], dtype=torch.uint8, device="cuda")
+    wsb = torch.empty(sizes["bwd"], dtype=torch.uint8, device="cuda")
+    y = moe.moe_fused_forward(shape, dev["x"], dev["w_gate"], dev["w_up"], dev["w_down"], routing,
+                              saved=saved, ws=ws)
+    g = moe.moe_fused_backward(shape, dev["dy"], dev["x"], dev["w_gate"], dev["w_up"],
+                               dev["w_down"], routing, saved, ws=wsb)
+    assert moe.moe_device_status(ws) == 0 and moe.moe_device_status(wsb) == 0
+    assert y.shape == (0, cfg.d) and g["dx"].shape == (0, cfg.d)
+    for key in ("dw_gate", "dw_up", "dw_down"):
+        assert (g[key] == 0).all(), key

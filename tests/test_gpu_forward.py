@@ -121,3 +121,12 @@ def test_forward_is_bitwise_repeatable_and_schedule_independent():
     for schedule, workers, tile_rows in ((2, 0, 0), (1, 7, 0), (1, 64, 0), (1, 0, 128), (1, 0, 256)):
         other, _, _ = gpu_forward(cfg, inp, schedule, tile_rows, with_saved=False, workers=workers)
         assert torch.equal(ref, other), (schedule, workers, tile_rows)
+
+
+def test_calibration_copy_copies():
+    import paper_2604_19241_amd as moe
+    src = torch.randint(0, 255, (3 * 1024 * 1024 + 16,), dtype=torch.uint8, device="cuda")
+    dst = torch.zeros_like(src)
+    moe.moe_calibration_copy(dst, src)
+    torch.cuda.synchronize()
+    assert torch.equal(dst, src)
