@@ -78,16 +78,18 @@ struct RowLoader {
     }
     // LDS row that pass p of this thread fills
     static __device__ __forceinline__ int row(int p) { return (threadIdx.x >> 3) + p * RPP; }
-    static constexpr int PP = NP / 4;          // passes per quarter-stage part
-    static_assert(NP % 4 == 0, "row loader needs a multiple of 4 passes");
+    // The whole stage moves in part 0, right behind the stage barrier: measured faster than
+    // a quarter of it ahead of every k-sub-step.
     __device__ __forceinline__ void gload_part(int s, int part) {
+        if (part != 0) return;
 #pragma unroll
-        for (int p = part * PP; p < (part + 1) * PP; ++p)
+        for (int p = 0; p < NP; ++p)
             reg[p] = *(const u32x4_t*)(rp[p] + (size_t)UNIEP_STAGE_OF(s) * (BK * 2));
     }
     __device__ __forceinline__ void sstore_part(char* base, int part) {
+        if (part != 0) return;
 #pragma unroll
-        for (int p = part * PP; p < (part + 1) * PP; ++p) {
+        for (int p = 0; p < NP; ++p) {
             u32x4_t r = reg[p];
             if (SCALE) {
                 const float f = sc[p];
@@ -116,17 +118,17 @@ struct SplitRowLoader {
         lds_off = (threadIdx.x >> 3) * kRowBytes + (threadIdx.x & 7) * 16;
     }
     static __device__ __forceinline__ int row(int p) { return (threadIdx.x >> 3) + p * RPP; }
-    static constexpr int PP = NP / 4;
-    static_assert(NP % 4 == 0, "row loader needs a multiple of 4 passes");
     __device__ __forceinline__ void gload_part(int s, int part) {
         const long long off = (s < switch_stage) ? (long long)s * (BK * 2)
                                                  : delta + (long long)(s - switch_stage) * (BK * 2);
+        if (part != 0) return;
 #pragma unroll
-        for (int p = part * PP; p < (part + 1) * PP; ++p) reg[p] = *(const u32x4_t*)(rp[p] + off);
+        for (int p = 0; p < NP; ++p) reg[p] = *(const u32x4_t*)(rp[p] + off);
     }
     __device__ __forceinline__ void sstore_part(char* base, int part) {
+        if (part != 0) return;
 #pragma unroll
-        for (int p = part * PP; p < (part + 1) * PP; ++p)
+        for (int p = 0; p < NP; ++p)
             *(u32x4_t*)(base + lds_off + p * RPP * kRowBytes) = reg[p];
     }
 };
@@ -298,9 +300,11 @@ __device__ __forceinline__ int tr_tile_row(int rho) {
 //
 // Pipeline: while stage t is multiplied out of LDS buffer t%2, the registers
 // that hold stage t+1 (fetched during stage t-1) are written to the other
-// buffer and immediately refilled with stage t+2.  Both happen in quarter-stage
-// parts between the four k-sub-steps, so global loads are issued continuously
-// and every load has a whole stage of matrix work to arrive.  One barrier per
+// buffer and immediately refilled with stage t+2, right behind the stage
+// barrier (the loaders take a part index 0..3, one per k-sub-step, and all of
+// them move the whole stage in part 0: spreading it over the sub-steps measured
+// slower), so every load has a whole stage of matrix work to arrive and every
+// LDS write a whole stage before the barrier that publishes it.  One barrier per
 // stage.  Stage indices past the end are clamped (a harmless re-read; the
 // extra LDS image is never consumed).
 // `active` = false lets a wave whose rows are all outside the tile skip the
