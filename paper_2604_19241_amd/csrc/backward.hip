@@ -44,10 +44,8 @@ struct BwdParams {
     char* dw_down;
     float* dtopk_w;
     int* ctrl;
-    RowTile* rt;
     int* flag_rt;   // per row tile: dH column tiles finished
     int* flag_e;    // per expert: dH tiles finished
-    int* need_e;    // per expert: dH tiles it has
     Task* tasks;
     int32_t* row_tok;
     float* row_w;
@@ -83,6 +81,7 @@ __global__ void __launch_bounds__(1024) bwd_prologue_kernel(BwdParams p) {
     __shared__ int32_t s_ga[kMaxExperts];
     __shared__ int32_t s_gb[kMaxExperts];
     __shared__ int32_t s_rt0[kMaxExperts];
+    __shared__ int32_t s_r0[kMaxExperts];
     __shared__ int32_t s_ta[kMaxExperts];
     __shared__ int32_t s_tb[kMaxExperts];
     __shared__ int32_t s_qbase[kQueues + 1];
@@ -131,18 +130,9 @@ __global__ void __launch_bounds__(1024) bwd_prologue_kernel(BwdParams p) {
     __syncthreads();
     if (e < ec) {
         const int rt0 = s_scan[e] - nt;
-        const int r0 = p.offsets[e];
-        for (int i = 0; i < nt; ++i) {
-            RowTile t;
-            t.expert = e;
-            t.row0 = r0 + i * BM;
-            t.rows = min(BM, cnt - i * BM);
-            t.pad = 0;
-            p.rt[rt0 + i] = t;
-            p.flag_rt[rt0 + i] = 0;
-        }
+        s_r0[e] = p.offsets[e];
+        for (int i = 0; i < nt; ++i) p.flag_rt[rt0 + i] = 0;
         p.flag_e[e] = 0;
-        p.need_e[e] = nt * p.nct_dh;
         int pa, pb;
         queue_positions(s_plan, s_ga, s_gb, e, s_lag, pa, pb);
         s_rt0[e] = rt0;
@@ -155,12 +145,19 @@ __global__ void __launch_bounds__(1024) bwd_prologue_kernel(BwdParams p) {
         const int n_dh = s_ga[x] - per_dwd, n_dxp = s_gb[x] - per_dwgu;
         Task* ta = p.tasks + s_ta[x];
         Task* tb = p.tasks + s_tb[x];
-        for (int i = lane; i < n_dh; i += 64) ta[i] = Task{rt0 + i / p.nct_dh, (B_DH << 20) | (i % p.nct_dh)};
+        const int r0 = s_r0[x], rows_x = s_plan.cost[x];
+        for (int i = lane; i < n_dh; i += 64) {
+            const int j = i / p.nct_dh;
+            ta[i] = Task{rt0 + j, task_code(B_DH, x, i % p.nct_dh), r0 + j * BM, min(BM, rows_x - j * BM)};
+        }
         for (int i = lane; i < per_dwd; i += 64)
-            ta[n_dh + i] = Task{x * p.mt_dwd + i / p.nt_dwd, (B_DWD << 20) | (i % p.nt_dwd)};
-        for (int i = lane; i < n_dxp; i += 64) tb[i] = Task{rt0 + i / p.nct_dxp, (B_DXP << 20) | (i % p.nct_dxp)};
+            ta[n_dh + i] = Task{i / p.nt_dwd, task_code(B_DWD, x, i % p.nt_dwd), r0, rows_x};
+        for (int i = lane; i < n_dxp; i += 64) {
+            const int j = i / p.nct_dxp;
+            tb[i] = Task{rt0 + j, task_code(B_DXP, x, i % p.nct_dxp), r0 + j * BM, min(BM, rows_x - j * BM)};
+        }
         for (int i = lane; i < per_dwgu; i += 64)
-            tb[n_dxp + i] = Task{x * p.mt_dwgu + i / p.nt_dwgu, (B_DWGU << 20) | (i % p.nt_dwgu)};
+            tb[n_dxp + i] = Task{i / p.nt_dwgu, task_code(B_DWGU, x, i % p.nt_dwgu), r0, rows_x};
     }
     if (e < CTRL_WORDS) {
         int v = 0;
@@ -273,11 +270,11 @@ __device__ __forceinline__ void dxp_task(const BwdParams& p, const RowTile rt, i
 // dW_down[e][i][c] = sum over the expert's rows r (ascending) of h[r][i] * dO[r][c].
 // Output tile: 32*NW rows of I by 256 columns of d.
 template <int NW>
-__device__ __forceinline__ void dwd_task(const BwdParams& p, int e, int mt, int nt, char* smem) {
+__device__ __forceinline__ void dwd_task(const BwdParams& p, int e, int mt, int nt, int r0, int cnt,
+                                         char* smem) {
     typedef Geom<NW> G;
     const int d = p.s.d, I = p.s.I;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int r0 = p.offsets[e], cnt = p.offsets[e + 1] - r0;
     typedef StridedLoaderK<G::NT, 4 * NW> AL;
     AL al;
     al.init();
@@ -311,11 +308,11 @@ __device__ __forceinline__ void dwd_task(const BwdParams& p, int e, int mt, int 
 // Output tile: 32*NW rows of d by 128 columns of I, for both matrices at once.
 // B-tile chunk nb: even -> 8 columns of dG, odd -> the same 8 columns of dU.
 template <int NW>
-__device__ __forceinline__ void dwgu_task(const BwdParams& p, int e, int mt, int nt, char* smem) {
+__device__ __forceinline__ void dwgu_task(const BwdParams& p, int e, int mt, int nt, int r0, int cnt,
+                                          char* smem) {
     typedef Geom<NW> G;
     const int d = p.s.d, I = p.s.I;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int r0 = p.offsets[e], cnt = p.offsets[e + 1] - r0;
     typedef GatherStridedLoader<G::NT, 4 * NW, false> AL;
     AL al;
     al.init();
@@ -422,6 +419,21 @@ __device__ __forceinline__ void dx_task(const BwdParams& p, int block) {
     }
 }
 
+#ifdef UNIEP_PROFILE_BWD   // timing experiments only: per-worker event trace {type, start, end, xcd}
+constexpr int kTraceEventsB = 160;
+__device__ long long g_trace_b[256][kTraceEventsB][4];
+#define TRACE_B(type) do { if (threadIdx.x == 0 && blockIdx.x < 256 && n_ev < kTraceEventsB) { \
+    g_trace_b[blockIdx.x][n_ev][0] = (type); g_trace_b[blockIdx.x][n_ev][1] = t_ev; \
+    g_trace_b[blockIdx.x][n_ev][2] = wall_clock64(); g_trace_b[blockIdx.x][n_ev][3] = home; } ++n_ev; } while (0)
+extern "C" int moe_debug_trace_bwd(long long* out) {
+    if (hipDeviceSynchronize() != hipSuccess) return MOE_ERR_HIP;
+    return hipMemcpyFromSymbol(out, HIP_SYMBOL(g_trace_b), sizeof(long long) * 256 * kTraceEventsB * 4) == hipSuccess
+               ? MOE_OK : MOE_ERR_HIP;
+}
+#else
+#define TRACE_B(type) do { } while (0)
+#endif
+
 // ------------------------------------------------------------- worker loop
 template <int NW>
 __global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
@@ -443,41 +455,53 @@ bwd_worker_kernel(BwdParams p, int phase) {
         s_task = fetch_task(ctrl, pass, home, exhausted, use_lists, use_tail);
     }
     __syncthreads();
+#ifdef UNIEP_PROFILE_BWD
+    int n_ev = 0;
+#endif
     for (;;) {
         const int id = s_task;
         if (id == kFetchDone) break;
+#ifdef UNIEP_PROFILE_BWD
+        const long long t_ev = wall_clock64();
+#endif
         PendingFetch pf;
         pf.q = -1;
         pf.id = 0;
         if (threadIdx.x == 0) pf = fetch_issue(ctrl, pass, home, exhausted, use_lists);
         if (id >= 0) {
             const Task task = p.tasks[id];
-            const int type = task.type_ct >> 20, ct = task.type_ct & 0xfffff;
+            const int type = task_type(task), ct = task_ct(task);
             if (phase >= 0 && type != phase) {
                 // staged launch: another phase's task
             } else if (type == B_DH) {
-                const RowTile rt = p.rt[task.rt];
+                const RowTile rt = task_row_tile(task);
                 dh_task<NW>(p, rt, ct, smem);
                 wait_stores();
                 __syncthreads();   // the write-through dG|dU stores of every wave have completed
                 if (threadIdx.x == 0) {
-                    add_relaxed(p.flag_rt + task.rt, 1);
+                    add_relaxed(p.flag_rt + task.idx, 1);
                     add_relaxed(p.flag_e + rt.expert, 1);
                 }
+                TRACE_B(B_DH + 16 * rt.rows);
             } else if (type == B_DWD) {
-                dwd_task<NW>(p, task.rt / p.mt_dwd, task.rt % p.mt_dwd, ct, smem);
+                dwd_task<NW>(p, task_expert(task), task.idx, ct, task.row0, task.rows, smem);
+                TRACE_B(B_DWD);
             } else if (type == B_DXP) {
-                if (threadIdx.x == 0) s_ok = wait_ge(p.flag_rt + task.rt, p.nct_dh, ctrl, p.spin_ticks);
+                if (threadIdx.x == 0) s_ok = wait_ge(p.flag_rt + task.idx, p.nct_dh, ctrl, p.spin_ticks);
                 __syncthreads();
                 if (s_ok) {
-                    const RowTile rt = p.rt[task.rt];
+                    const RowTile rt = task_row_tile(task);
                     dxp_task<NW>(p, rt, ct, smem);
+                    TRACE_B(B_DXP + 16 * rt.rows);
                 }
             } else {
-                const int e = task.rt / p.mt_dwgu;
-                if (threadIdx.x == 0) s_ok = wait_ge(p.flag_e + e, p.need_e[e], ctrl, p.spin_ticks);
+                const int e = task_expert(task);
+                // all dH tiles of the expert: its row tiles times the dH column tiles
+                const int need = (task.rows + Geom<NW>::BM - 1) / Geom<NW>::BM * p.nct_dh;
+                if (threadIdx.x == 0) s_ok = wait_ge(p.flag_e + e, need, ctrl, p.spin_ticks);
                 __syncthreads();
-                if (s_ok) dwgu_task<NW>(p, e, task.rt % p.mt_dwgu, ct, smem);
+                if (s_ok) dwgu_task<NW>(p, e, task.idx, ct, task.row0, task.rows, smem);
+                TRACE_B(B_DWGU);
             }
         } else {
             if (publishes && !arrived) {
@@ -492,7 +516,9 @@ bwd_worker_kernel(BwdParams p, int phase) {
             if (threadIdx.x == 0)
                 s_ok = wait_ge(ctrl + CTRL_DONE, ctrl[CTRL_NWAIT], ctrl, p.spin_ticks, CTRL_TAIL_WAIT_TICKS);
             __syncthreads();
+            TRACE_B(5);   // wait ahead of a tail task
             if (s_ok) dx_task<NW>(p, -1 - id);
+            TRACE_B(B_DX);
         }
         __syncthreads();
         if (threadIdx.x == 0) s_task = fetch_finish(pf, ctrl, pass, home, exhausted, use_lists, use_tail);
@@ -511,7 +537,7 @@ bwd_worker_kernel(BwdParams p, int phase) {
 // ------------------------------------------------------------------ host side
 
 struct BwdLayout {
-    size_t ctrl, rt, flag_rt, flag_e, need_e, tasks, row_tok, row_w, dgu, dxp, total;
+    size_t ctrl, flag_rt, flag_e, tasks, row_tok, row_w, dgu, dxp, total;
     int max_rt, nct_dh, nct_dxp, mt_dwd, nt_dwd, mt_dwgu, nt_dwgu;
 };
 
@@ -530,10 +556,8 @@ static BwdLayout bwd_layout(const moe_shape_t& s, int bm) {
                              (s.T + kDxTokens - 1) / kDxTokens;
     size_t off = 0;
     L.ctrl = off;    off = align_up(off + CTRL_WORDS * sizeof(int), 256);
-    L.rt = off;      off = align_up(off + (size_t)L.max_rt * sizeof(RowTile), 256);
     L.flag_rt = off; off = align_up(off + (size_t)L.max_rt * sizeof(int), 256);
     L.flag_e = off;  off = align_up(off + (size_t)s.e_count * sizeof(int), 256);
-    L.need_e = off;  off = align_up(off + (size_t)s.e_count * sizeof(int), 256);
     L.tasks = off;   off = align_up(off + max_tasks * sizeof(Task), 256);
     L.row_tok = off; off = align_up(off + A_cap * sizeof(int32_t), 256);
     L.row_w = off;   off = align_up(off + A_cap * sizeof(float), 256);
@@ -617,10 +641,8 @@ int bwd_launch(const moe_shape_t& s, const void* dy, const void* x, const void* 
     p.dw_down = (char*)dw_down;
     p.dtopk_w = dtopk_w;
     p.ctrl = (int*)(ws + L.ctrl);
-    p.rt = (RowTile*)(ws + L.rt);
     p.flag_rt = (int*)(ws + L.flag_rt);
     p.flag_e = (int*)(ws + L.flag_e);
-    p.need_e = (int*)(ws + L.need_e);
     p.tasks = (Task*)(ws + L.tasks);
     p.row_tok = (int32_t*)(ws + L.row_tok);
     p.row_w = (float*)(ws + L.row_w);

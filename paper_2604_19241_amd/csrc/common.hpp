@@ -320,13 +320,23 @@ struct RowTile {   // one row tile of one local expert
     int32_t expert;  // local expert id
     int32_t row0;    // first row (position in the expert-sorted order)
     int32_t rows;    // valid rows in this tile (1..BM)
-    int32_t pad;
 };
 
+// One GEMM task, self-contained so that a worker needs a single 16-byte load
+// before it can start: no second trip to a row-tile table or to the offsets.
 struct Task {
-    int32_t rt;       // row tile (GEMM phases) or block index (combine phases)
-    int32_t type_ct;  // (type << 20) | column tile
+    int32_t idx;      // row-tile tasks: row tile index (its scoreboard flag); weight-gradient tasks: row-tile of the output (m index)
+    int32_t code;     // (type << 28) | (local expert << 16) | column tile
+    int32_t row0;     // row-tile tasks: first row of the tile; weight-gradient tasks: first row of the expert
+    int32_t rows;     // row-tile tasks: rows in the tile; weight-gradient tasks: rows of the expert (the reduction length)
 };
+__host__ __device__ __forceinline__ int32_t task_code(int type, int expert, int ct) {
+    return (int32_t)(((uint32_t)type << 28) | ((uint32_t)expert << 16) | (uint32_t)ct);
+}
+__device__ __forceinline__ int task_type(const Task& t) { return (int)((uint32_t)t.code >> 28); }
+__device__ __forceinline__ int task_expert(const Task& t) { return (t.code >> 16) & 0xfff; }
+__device__ __forceinline__ int task_ct(const Task& t) { return t.code & 0xffff; }
+__device__ __forceinline__ RowTile task_row_tile(const Task& t) { return RowTile{task_expert(t), t.row0, t.rows}; }
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 

@@ -55,7 +55,6 @@ struct FwdParams {
     char* h;    // [A,I]
     char* o;    // [A,d]
     int* ctrl;
-    RowTile* rt;
     int* flag1;   // per row tile: GEMM1 column tiles finished
     Task* tasks;
     int nct1, nct2;   // column tiles of GEMM1 (128 h-columns each) and GEMM2 (256 each)
@@ -117,20 +116,13 @@ __global__ void __launch_bounds__(1024) fwd_prologue_kernel(FwdParams p) {
     }
     __syncthreads();
     __shared__ int32_t s_rt0[kMaxExperts];
+    __shared__ int32_t s_r0[kMaxExperts];
     __shared__ int32_t s_t1[kMaxExperts];
     __shared__ int32_t s_t2[kMaxExperts];
     if (e < ec) {
         const int rt0 = s_scan[e] - nt;
-        const int r0 = p.offsets[e];
-        for (int i = 0; i < nt; ++i) {
-            RowTile t;
-            t.expert = e;
-            t.row0 = r0 + i * BM;
-            t.rows = min(BM, cnt - i * BM);
-            t.pad = 0;
-            p.rt[rt0 + i] = t;
-            p.flag1[rt0 + i] = 0;
-        }
+        s_r0[e] = p.offsets[e];
+        for (int i = 0; i < nt; ++i) p.flag1[rt0 + i] = 0;
         int pos1, pos2;
         queue_positions(s_plan, s_g1, s_g2, e, s_lag, pos1, pos2);
         s_rt0[e] = rt0;
@@ -143,8 +135,15 @@ __global__ void __launch_bounds__(1024) fwd_prologue_kernel(FwdParams p) {
         Task* t1 = p.tasks + s_t1[x];
         Task* t2 = p.tasks + s_t2[x];
         const int n1 = s_g1[x], n2 = s_g2[x];
-        for (int i = lane; i < n1; i += 64) t1[i] = Task{rt0 + i / p.nct1, (TASK_GEMM1 << 20) | (i % p.nct1)};
-        for (int i = lane; i < n2; i += 64) t2[i] = Task{rt0 + i / p.nct2, (TASK_GEMM2 << 20) | (i % p.nct2)};
+        const int r0 = s_r0[x], rows_x = s_plan.cost[x];
+        for (int i = lane; i < n1; i += 64) {
+            const int j = i / p.nct1;
+            t1[i] = Task{rt0 + j, task_code(TASK_GEMM1, x, i % p.nct1), r0 + j * BM, min(BM, rows_x - j * BM)};
+        }
+        for (int i = lane; i < n2; i += 64) {
+            const int j = i / p.nct2;
+            t2[i] = Task{rt0 + j, task_code(TASK_GEMM2, x, i % p.nct2), r0 + j * BM, min(BM, rows_x - j * BM)};
+        }
     }
     if (e < CTRL_WORDS) {
         int v = 0;
@@ -382,11 +381,11 @@ fwd_worker_kernel(FwdParams p, int phase) {
         if (threadIdx.x == 0) pf = fetch_issue(ctrl, pass, home, exhausted, use_lists);
         if (id >= 0) {
             const Task task = p.tasks[id];
-            const int type = task.type_ct >> 20, ct = task.type_ct & 0xfffff;
+            const int type = task_type(task), ct = task_ct(task);
             if (phase >= 0 && type != phase) {
                 // staged launch: another phase's task, nothing to do
             } else if (type == TASK_GEMM1) {
-                const RowTile rt = p.rt[task.rt];
+                const RowTile rt = task_row_tile(task);
 #ifdef UNIEP_PROFILE
                 if (rt.rows == Geom<NW>::BM) PROF_ADD(TASK_GEMM1, 4, PROF_NOW() - t_ev);
                 const long long t_g1 = PROF_NOW();
@@ -394,16 +393,16 @@ fwd_worker_kernel(FwdParams p, int phase) {
                 gemm1_task<NW>(p, rt, ct, smem);
                 wait_stores();
                 __syncthreads();   // the write-through h stores of every wave have completed
-                if (threadIdx.x == 0) add_relaxed(p.flag1 + task.rt, 1);
+                if (threadIdx.x == 0) add_relaxed(p.flag1 + task.idx, 1);
 #ifdef UNIEP_PROFILE
                 if (rt.rows == Geom<NW>::BM) PROF_ADD(TASK_GEMM1, 6, PROF_NOW() - t_g1);
 #endif
                 TRACE_EVENT(n_ev, TASK_GEMM1 + 16 * rt.rows, t_ev);
             } else {
-                if (threadIdx.x == 0) s_ok = wait_ge(p.flag1 + task.rt, p.nct1, ctrl, p.spin_ticks);
+                if (threadIdx.x == 0) s_ok = wait_ge(p.flag1 + task.idx, p.nct1, ctrl, p.spin_ticks);
                 __syncthreads();
                 if (s_ok) {
-                    const RowTile rt = p.rt[task.rt];
+                    const RowTile rt = task_row_tile(task);
                     gemm2_task<NW>(p, rt, ct, smem);
                     TRACE_EVENT(n_ev, TASK_GEMM2 + 16 * rt.rows, t_ev);
                 }
@@ -442,7 +441,7 @@ fwd_worker_kernel(FwdParams p, int phase) {
 // ------------------------------------------------------------------ host side
 
 struct FwdLayout {
-    size_t ctrl, rt, flag1, tasks, h, o, total;
+    size_t ctrl, flag1, tasks, h, o, total;
     int max_rt, nct1, nct2;
     size_t max_tasks;
 };
@@ -456,7 +455,6 @@ FwdLayout fwd_layout(const moe_shape_t& s, bool with_ho) {
     L.max_tasks = (size_t)L.max_rt * (L.nct1 + L.nct2) + (s.T + kCombineTokens - 1) / kCombineTokens;
     size_t off = 0;
     L.ctrl = off;  off = align_up(off + CTRL_WORDS * sizeof(int), 256);
-    L.rt = off;    off = align_up(off + (size_t)L.max_rt * sizeof(RowTile), 256);
     L.flag1 = off; off = align_up(off + (size_t)L.max_rt * sizeof(int), 256);
     L.tasks = off; off = align_up(off + L.max_tasks * sizeof(Task), 256);
     L.h = off;     if (with_ho) off = align_up(off + A_cap * s.I * 2, 256);
@@ -531,7 +529,6 @@ int fwd_launch(const moe_shape_t& s, const void* x, const void* w_gate, const vo
     p.h = h;
     p.o = o;
     p.ctrl = (int*)(ws + L.ctrl);
-    p.rt = (RowTile*)(ws + L.rt);
     p.flag1 = (int*)(ws + L.flag1);
     p.tasks = (Task*)(ws + L.tasks);
     p.nct1 = L.nct1;
