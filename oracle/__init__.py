@@ -117,6 +117,23 @@ def route(shape: dict, logits: np.ndarray, acc: str = "f64") -> dict:
     return out
 
 
+def route_backward(shape: dict, logits: np.ndarray, topk_idx: np.ndarray, dtopk_w: np.ndarray,
+                   acc: str = "f64") -> np.ndarray:
+    """dlogits [T,E] (float64): gradient of the gates with respect to the logits, selection fixed."""
+    lib = _load(acc)
+    sh = _shape_arr(shape)
+    T, E, k = int(shape["T"]), int(shape["E"]), int(shape["k"])
+    logits = np.ascontiguousarray(logits, dtype=np.float32)
+    idx = np.ascontiguousarray(topk_idx, dtype=np.int32)
+    g = np.ascontiguousarray(dtopk_w, dtype=np.float32)
+    assert logits.shape == (T, E) and idx.shape == (T, k) and g.shape == (T, k)
+    out = np.empty((T, E), np.float64)
+    rc = getattr(lib, f"oracle_route_backward_{acc}")(_p(sh), _p(logits), _p(idx), _p(g), _p(out))
+    if rc != 0:
+        raise ValueError("oracle_route_backward: bad shape")
+    return out
+
+
 def forward(shape: dict, x, w_gate, w_up, w_down, routing: dict, round_bf16: bool = True,
             acc: str = "f64", stages: bool = False) -> dict:
     """y [T,d]; with stages=True also G,U,h [A,I] and o [A,d] (row order)."""

@@ -22,6 +22,8 @@
  *   backward  the calculus of the above; weight gradients reduce over an
  *             expert's rows in row order (the "Transposed GroupGEMM" of
  *             Section 2.1, whose accumulation order the token mapping fixes).
+ *   route_backward  gradient of the gates with respect to the logits for the
+ *             fixed selection, chain rule through renormalisation and softmax.
  *
  * Precision: the accumulate type is ACC_T (this file is built twice, as
  * double and as float).  With round_bf16 != 0 every value the pipeline hands
@@ -595,6 +597,48 @@ int FN(oracle_backward_tokens)(const int32_t* sh, int in_dtype, const void* x, c
         free(xr);
         expert_free(&w);
     }
+    return 0;
+}
+
+/* ---------------------------------------------------------- router gradient
+ * Gradient of the gates with respect to the logits, for a fixed selection
+ * (Section 2.1: gating scores; the selection itself is piecewise constant).
+ * The gate of slot j is  w_j = p_{e_j} / S,  p = softmax(logits[t, :]) over all
+ * E experts,  S = sum of p over the k selected experts.  Chain rule, written
+ * out without simplification: first the gradient with respect to p, then
+ * through the softmax.  dlogits is [T,E] in double. */
+int FN(oracle_route_backward)(const int32_t* sh, const float* logits, const int32_t* topk_idx,
+                              const float* dtopk_w, double* dlogits) {
+    const int T = sh[SH_T], E = sh[SH_E], k = sh[SH_K];
+    acc_t* p = (acc_t*)malloc(sizeof(acc_t) * (size_t)E);
+    acc_t* dp = (acc_t*)malloc(sizeof(acc_t) * (size_t)E);
+    for (int t = 0; t < T; ++t) {
+        const float* row = logits + (size_t)t * E;
+        const int32_t* sel = topk_idx + (size_t)t * k;
+        const float* g = dtopk_w + (size_t)t * k;
+        acc_t mx = (acc_t)row[0];
+        for (int e = 1; e < E; ++e)
+            if ((acc_t)row[e] > mx) mx = (acc_t)row[e];
+        acc_t den = 0;
+        for (int e = 0; e < E; ++e) {
+            p[e] = (acc_t)exp((double)((acc_t)row[e] - mx));
+            den += p[e];
+        }
+        for (int e = 0; e < E; ++e) p[e] = p[e] / den;
+        acc_t S = 0;
+        for (int j = 0; j < k; ++j) S += p[sel[j]];
+        /* d loss / d p_a : w_j = p_{e_j} / S */
+        acc_t cross = 0;
+        for (int j = 0; j < k; ++j) cross += (acc_t)g[j] * p[sel[j]];
+        for (int e = 0; e < E; ++e) dp[e] = 0;
+        for (int j = 0; j < k; ++j) dp[sel[j]] = (acc_t)g[j] / S - cross / (S * S);
+        /* through the softmax: d p_a / d l_e = p_a (delta_ae - p_e) */
+        acc_t dot = 0;
+        for (int a = 0; a < E; ++a) dot += dp[a] * p[a];
+        for (int e = 0; e < E; ++e) dlogits[(size_t)t * E + e] = (double)(p[e] * (dp[e] - dot));
+    }
+    free(p);
+    free(dp);
     return 0;
 }
 

@@ -169,3 +169,71 @@ def test_bad_shapes_rejected(oracle_mod):
         oracle_mod.route(shape(4, 4, 5), np.zeros((4, 4), np.float32))
     with pytest.raises(ValueError):
         oracle_mod.route(shape(4, 4, 2, 3, 2), np.zeros((4, 4), np.float32))
+
+
+# ------------------------------------------------------------------ router gradient
+
+def _gates_torch(logits, idx):
+    import torch
+    p = torch.softmax(logits, dim=-1)
+    sel = torch.gather(p, 1, idx)
+    return sel / sel.sum(dim=1, keepdim=True)
+
+
+def test_route_backward_matches_autograd_and_finite_differences(oracle_mod):
+    """Library pin (torch.autograd over the gate definition in float64) and central finite
+    differences; a wrong sign, a dropped renormalisation term or a transposed index fails both."""
+    import torch
+    rng = np.random.default_rng(5)
+    T, E, k = 7, 12, 4
+    shape = dict(T=T, d=64, E=E, k=k, I=64, e_start=0, e_count=E)
+    logits = rng.normal(0, 1.5, (T, E)).astype(np.float32)
+    r = oracle_mod.route(shape, logits)
+    g = rng.normal(0, 1, (T, k)).astype(np.float32)
+    got = oracle_mod.route_backward(shape, logits, r["topk_idx"], g)
+
+    lt = torch.tensor(logits, dtype=torch.float64, requires_grad=True)
+    idx = torch.tensor(r["topk_idx"], dtype=torch.int64)
+    w = _gates_torch(lt, idx)
+    (w * torch.tensor(g, dtype=torch.float64)).sum().backward()
+    assert np.allclose(got, lt.grad.numpy(), rtol=1e-9, atol=1e-12)
+
+    def loss(l):
+        with torch.no_grad():
+            return float((_gates_torch(torch.tensor(l, dtype=torch.float64), idx)
+                          * torch.tensor(g, dtype=torch.float64)).sum())
+    eps = 1e-5
+    l64 = logits.astype(np.float64)
+    for (t, e) in [(0, 0), (3, int(r["topk_idx"][3, 0])), (6, int(r["topk_idx"][6, k - 1])), (2, 5)]:
+        lp, lm = l64.copy(), l64.copy()
+        lp[t, e] += eps
+        lm[t, e] -= eps
+        fd = (loss(lp) - loss(lm)) / (2 * eps)
+        assert abs(fd - got[t, e]) <= 1e-7 + 1e-6 * abs(fd), (t, e, fd, got[t, e])
+
+
+def test_route_backward_closed_forms(oracle_mod):
+    """Unselected logits do not move the gates; the gradient of every row sums to zero (gates are
+    invariant under a shift of the row); k = 1 gives a constant gate, so a zero gradient; equal
+    upstream gradients give zero (the gates sum to one)."""
+    rng = np.random.default_rng(6)
+    T, E, k = 9, 10, 3
+    shape = dict(T=T, d=64, E=E, k=k, I=64, e_start=0, e_count=E)
+    logits = rng.normal(0, 1, (T, E)).astype(np.float32)
+    r = oracle_mod.route(shape, logits)
+    g = rng.normal(0, 1, (T, k)).astype(np.float32)
+    d = oracle_mod.route_backward(shape, logits, r["topk_idx"], g)
+    mask = np.zeros((T, E), bool)
+    np.put_along_axis(mask, r["topk_idx"].astype(np.int64), True, axis=1)
+    assert np.abs(d[~mask]).max() <= 1e-15
+    assert np.abs(d.sum(1)).max() <= 1e-14
+    # closed form on the selected entries: w_i (g_i - sum_j w_j g_j)
+    w = r["topk_w"].astype(np.float64)
+    want = w * (g - (w * g).sum(1, keepdims=True))
+    assert np.allclose(np.take_along_axis(d, r["topk_idx"].astype(np.int64), 1), want, rtol=1e-6, atol=1e-9)
+    same = oracle_mod.route_backward(shape, logits, r["topk_idx"], np.full((T, k), 0.7, np.float32))
+    assert np.abs(same).max() <= 1e-15
+    shape1 = dict(shape, k=1)
+    r1 = oracle_mod.route(shape1, logits)
+    d1 = oracle_mod.route_backward(shape1, logits, r1["topk_idx"], rng.normal(0, 1, (T, 1)).astype(np.float32))
+    assert np.abs(d1).max() <= 1e-15
