@@ -144,6 +144,19 @@ int moe_fused_backward(const moe_shape_t* shape, const void* dy, const void* x,
                        void* dw_up, void* dw_down, float* dtopk_w, void* ws, size_t ws_bytes,
                        const moe_opts_t* opts, void* stream);
 
+/* Gradient of the gates with respect to the router logits, for the selection
+ * that moe_route made (Section 2.1: the gating scores weight the expert
+ * outputs; with dtopk_w from moe_fused_backward this makes the layer trainable
+ * end to end).  For token t and its slots i:  dlogits[t, topk_idx[t,i]] =
+ * topk_w[t,i] * (dtopk_w[t,i] - sum_j topk_w[t,j] * dtopk_w[t,j]);  all other
+ * entries of the row are zero (the softmax denominator over all experts cancels
+ * in the renormalised gates, so unselected logits do not move them).
+ *   topk_idx [T,k] int32, topk_w [T,k] fp32, dtopk_w [T,k] fp32 (device, read)
+ *   dlogits  [T,E] fp32 (device, every element written)
+ * No workspace.  Returns MOE_ERR_ARG for NULL pointers when T > 0. */
+int moe_route_backward(const moe_shape_t* shape, const int32_t* topk_idx, const float* topk_w,
+                       const float* dtopk_w, float* dlogits, void* stream);
+
 /* Synchronises `stream`, reads the status word a forward/backward call left in
  * its workspace and returns MOE_OK or MOE_ERR_DEVICE (test and debug aid; the
  * hot path never calls it). */

@@ -9,6 +9,7 @@ from __future__ import annotations
 import ctypes
 from dataclasses import dataclass
 from pathlib import Path
+from typing import Optional
 
 import torch
 
@@ -19,7 +20,8 @@ MOE_OK = 0
 MOE_ERR_ARG, MOE_ERR_SHAPE, MOE_ERR_WORKSPACE, MOE_ERR_HIP, MOE_ERR_DEVICE = -1, -2, -3, -4, -5
 
 EXPORTS = ("moe_workspace_bytes", "moe_saved_layout", "moe_route", "moe_fused_forward",
-           "moe_fused_backward", "moe_device_status", "moe_status_string", "moe_calibration_copy")
+           "moe_fused_backward", "moe_route_backward", "moe_device_status", "moe_status_string",
+           "moe_calibration_copy")
 
 
 class MoEShape(ctypes.Structure):
@@ -188,6 +190,20 @@ def moe_fused_backward(shape: MoEShape, dy, x, w_gate, w_up, w_down, routing: Ro
         ctypes.byref(cs), _ptr(saved), _ptr(out["dx"]), _ptr(out["dw_gate"]), _ptr(out["dw_up"]),
         _ptr(out["dw_down"]), _ptr(out.get("dtopk_w")), _ptr(ws), ctypes.c_size_t(ws.numel()),
         ctypes.byref(opts) if opts is not None else None, _stream(dev)), "moe_fused_backward")
+    return out
+
+
+def moe_route_backward(shape: MoEShape, routing: "Routing", dtopk_w: torch.Tensor,
+                       out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """dlogits [T,E] fp32 from the gate gradients dtopk_w [T,k] fp32 and the routing moe_route made."""
+    dev = dtopk_w.device
+    assert dtopk_w.dtype == torch.float32 and dtopk_w.is_contiguous()
+    if out is None:
+        out = torch.empty((shape.T, shape.E), dtype=torch.float32, device=dev)
+    lib = load_library()
+    lib.moe_route_backward.argtypes = [ctypes.c_void_p] * 6
+    _check(lib.moe_route_backward(ctypes.byref(shape), _ptr(routing.topk_idx), _ptr(routing.topk_w),
+                                  _ptr(dtopk_w), _ptr(out), _stream(dev)), "moe_route_backward")
     return out
 
 

@@ -6,6 +6,8 @@
 
 namespace uniep {
 size_t route_workspace_bytes(const moe_shape_t& s);
+int route_backward_launch(const moe_shape_t& s, const int32_t* topk_idx, const float* topk_w,
+                          const float* dtopk_w, float* dlogits, hipStream_t st);
 int route_launch(const moe_shape_t& s, const float* logits, const moe_routing_t& out, void* ws,
                  hipStream_t st);
 size_t fwd_workspace_bytes(const moe_shape_t& s);
@@ -201,6 +203,16 @@ int moe_fused_backward(const moe_shape_t* shape, const void* dy, const void* x, 
     return bwd_launch(*shape, dy, x, w_gate, w_up, w_down, *routing, sv + L.gu, sv + L.h, sv + L.o,
                       dx, dw_gate, dw_up, dw_down, dtopk_w, (char*)ws, o, pick_nw(*shape, o),
                       (hipStream_t)stream);
+}
+
+int moe_route_backward(const moe_shape_t* shape, const int32_t* topk_idx, const float* topk_w,
+                       const float* dtopk_w, float* dlogits, void* stream) {
+    int rc = check_shape(shape);
+    if (rc != MOE_OK) return rc;
+    if (shape->T > 0 && (!topk_idx || !topk_w || !dtopk_w || !dlogits)) return MOE_ERR_ARG;
+    if (!aligned(topk_idx, 4) || !aligned(topk_w, 4) || !aligned(dtopk_w, 4) || !aligned(dlogits, 4))
+        return MOE_ERR_ARG;
+    return route_backward_launch(*shape, topk_idx, topk_w, dtopk_w, dlogits, (hipStream_t)stream);
 }
 
 int moe_device_status(const void* ws, void* stream) {

@@ -214,7 +214,49 @@ position_kernel(const int32_t* __restrict__ topk_idx, int F, int e_start, int e_
     }
 }
 
+// ------------------------------------------------------------ router gradient
+// One wave per token.  Lanes j < k hold slot j; s = sum_j w_j g_j by a wave
+// reduction; then every lane writes its experts of the row: the value of the
+// slot that selected the expert, or zero.
+__global__ void __launch_bounds__(kRouteThreads)
+route_backward_kernel(const int32_t* __restrict__ topk_idx, const float* __restrict__ topk_w,
+                      const float* __restrict__ dtopk_w, int T, int E, int k,
+                      float* __restrict__ dlogits) {
+    const int lane = threadIdx.x & 63;
+    const int t = blockIdx.x * (kRouteThreads / 64) + (threadIdx.x >> 6);
+    if (t >= T) return;
+    int idx = -1;
+    float w = 0.f, g = 0.f;
+    if (lane < k) {
+        idx = topk_idx[(size_t)t * k + lane];
+        w = topk_w[(size_t)t * k + lane];
+        g = dtopk_w[(size_t)t * k + lane];
+    }
+    float s = w * g;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) s += __shfl_xor(s, off);
+    const float mine = w * (g - s);
+    for (int e = lane; e < E; e += 64) {
+        float v = 0.f;
+        for (int j = 0; j < k; ++j) {
+            const int ej = __shfl(idx, j);
+            const float vj = __shfl(mine, j);
+            if (ej == e) v = vj;
+        }
+        dlogits[(size_t)t * E + e] = v;
+    }
+}
+
 // ------------------------------------------------------------------ host side
+
+int route_backward_launch(const moe_shape_t& s, const int32_t* topk_idx, const float* topk_w,
+                          const float* dtopk_w, float* dlogits, hipStream_t st) {
+    if (s.T == 0) return MOE_OK;
+    const int per = kRouteThreads / 64;
+    hipLaunchKernelGGL(route_backward_kernel, dim3((s.T + per - 1) / per), dim3(kRouteThreads), 0, st,
+                       topk_idx, topk_w, dtopk_w, s.T, s.E, s.k, dlogits);
+    return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
+}
 
 size_t route_workspace_bytes(const moe_shape_t& s) {
     const size_t F = (size_t)s.T * s.k;

@@ -21,8 +21,9 @@ def lib():
 def test_every_declared_symbol_is_exported(lib):
     header = (ROOT / "include" / "uniep_moe.h").read_text()
     names = set(re.findall(r"^(?:int|const char\*)\s+(moe_\w+)\s*\(", header, flags=re.M))
-    assert {"moe_route", "moe_fused_forward", "moe_fused_backward", "moe_workspace_bytes",
-            "moe_saved_layout", "moe_device_status", "moe_status_string"} <= names
+    assert {"moe_route", "moe_fused_forward", "moe_fused_backward", "moe_route_backward",
+            "moe_workspace_bytes", "moe_saved_layout", "moe_device_status", "moe_status_string",
+            "moe_calibration_copy"} <= names
     for n in names:
         assert hasattr(lib, n), n
 

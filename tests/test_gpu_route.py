@@ -92,3 +92,32 @@ def test_route_empty_batch():
     torch.cuda.synchronize()
     assert r.counts.cpu().tolist() == [0] * 8
     assert r.offsets.cpu().tolist() == [0] * 9
+
+
+@pytest.mark.parametrize("kw", [
+    dict(T=300, d=64, E=128, k=8, I=64),
+    dict(T=65, d=64, E=1024, k=16, I=64),
+    dict(T=129, d=64, E=5, k=5, I=64),
+    dict(T=40, d=64, E=7, k=1, I=64),
+])
+def test_route_backward_matches_oracle(kw):
+    """dlogits from the gate gradients: parity with the oracle (fp32 arithmetic on the GPU, the
+    gates themselves are fp32: rtol 1e-5), exact zeros for unselected experts."""
+    import paper_2604_19241_amd as moe
+    cfg = moe_synth.small_config(**kw)
+    say(f"[route-bwd] {cfg.shape_dict()}")
+    rng = np.random.default_rng(17)
+    logits = rng.normal(0, 1.5, (cfg.T, cfg.E)).astype(np.float32)
+    g = rng.normal(0, 1, (cfg.T, cfg.k)).astype(np.float32)
+    want_r = oracle.route(cfg.shape_dict(), logits)
+    want = oracle.route_backward(cfg.shape_dict(), logits, want_r["topk_idx"], g)
+    shape = moe.make_shape(**cfg.shape_dict())
+    routing = moe.moe_route(shape, torch.from_numpy(logits).cuda())
+    got = moe.moe_route_backward(shape, routing, torch.from_numpy(g).cuda())
+    torch.cuda.synchronize()
+    got = got.cpu().numpy().astype(np.float64)
+    assert np.array_equal(routing.topk_idx.cpu().numpy(), want_r["topk_idx"])
+    mask = np.zeros((cfg.T, cfg.E), bool)
+    np.put_along_axis(mask, want_r["topk_idx"].astype(np.int64), True, axis=1)
+    assert (got[~mask] == 0).all()
+    assert np.allclose(got, want, rtol=1e-5, atol=2e-7), np.abs(got - want).max()
