@@ -289,6 +289,7 @@ __device__ __forceinline__ void dwd_task(const BwdParams& p, int e, int mt, int 
     bl.row_w = p.row_w;
     bl.row0 = r0;
     bl.K = cnt;
+    bl.ring = smem + G::SMEM;
     bl.src = p.dy + (size_t)min(nt * BN + BL::TG::chunk() * 8, d - 8) * 2;
     f32x16_t acc[8];
     mma_mainloop<NW>(al, bl, (cnt + BK - 1) / BK, smem, true, acc);
@@ -321,6 +322,7 @@ __device__ __forceinline__ void dwgu_task(const BwdParams& p, int e, int mt, int
     al.row_w = p.row_w;
     al.row0 = r0;
     al.K = cnt;
+    al.ring = smem + G::SMEM;
     al.src = p.x + (size_t)min(mt * G::BM + AL::TG::chunk() * 8, d - 8) * 2;
     typedef StridedLoaderK<G::NT, 32> BL;
     BL bl;
@@ -579,11 +581,11 @@ static int bwd_resident_workers(int* out) {
     if (g_bwd_workers[slot] == 0) {
         if (hipFuncSetAttribute((const void*)bwd_worker_kernel<NW>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize,
-                                Geom<NW>::SMEM) != hipSuccess)
+                                Geom<NW>::SMEM + kIdxRingBytes) != hipSuccess)
             return MOE_ERR_HIP;
         int per_cu = 0, cus = 0;
         if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, bwd_worker_kernel<NW>, Geom<NW>::NT,
-                                                         Geom<NW>::SMEM) != hipSuccess)
+                                                         Geom<NW>::SMEM + kIdxRingBytes) != hipSuccess)
             return MOE_ERR_HIP;
         if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
             return MOE_ERR_HIP;
@@ -608,10 +610,10 @@ static int bwd_launch_nw(BwdParams& p, const moe_opts_t& opts, hipStream_t st) {
     if (opts.schedule == 2) {
         for (int phase = 0; phase < 5; ++phase)
             hipLaunchKernelGGL(bwd_worker_kernel<NW>, dim3(workers), dim3(Geom<NW>::NT),
-                               Geom<NW>::SMEM, st, p, phase);
+                               Geom<NW>::SMEM + kIdxRingBytes, st, p, phase);
     } else {
-        hipLaunchKernelGGL(bwd_worker_kernel<NW>, dim3(workers), dim3(Geom<NW>::NT), Geom<NW>::SMEM,
-                           st, p, -1);
+        hipLaunchKernelGGL(bwd_worker_kernel<NW>, dim3(workers), dim3(Geom<NW>::NT),
+                           Geom<NW>::SMEM + kIdxRingBytes, st, p, -1);
     }
     return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }

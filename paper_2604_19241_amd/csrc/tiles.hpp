@@ -66,6 +66,8 @@ __device__ __forceinline__ u32x4_t zero4() { return u32x4_t{0u, 0u, 0u, 0u}; }
 // SCALE: multiply the row by a per-row fp32 factor and round to bf16 once.
 template <int NT, int NROWS, bool SCALE>
 struct RowLoader {
+    static constexpr bool kNeedsPrime = false;
+    __device__ __forceinline__ void prime() {}
     static constexpr int RPP = NT / 8;         // rows per pass
     static constexpr int NP = NROWS / RPP;     // passes
     const char* rp[NP];
@@ -106,6 +108,8 @@ struct RowLoader {
 // second matrix, which sits `delta` bytes after the first.
 template <int NT, int NROWS>
 struct SplitRowLoader {
+    static constexpr bool kNeedsPrime = false;
+    __device__ __forceinline__ void prime() {}
     static constexpr int RPP = NT / 8;
     static constexpr int NP = NROWS / RPP;
     const char* rp[NP];
@@ -177,6 +181,8 @@ struct TrGeom {
 template <int NT, int NCH>
 struct StridedLoader {
     typedef TrGeom<NT, NCH> TG;
+    static constexpr bool kNeedsPrime = false;
+    __device__ __forceinline__ void prime() {}
     const char* bp;
     size_t ld_bytes;
     u32x4_t reg[TG::KR];
@@ -205,6 +211,8 @@ struct StridedLoader {
 template <int NT, int NCH>
 struct StridedLoaderK {
     typedef TrGeom<NT, NCH> TG;
+    static constexpr bool kNeedsPrime = false;
+    __device__ __forceinline__ void prime() {}
     const char* bp;
     size_t ld_bytes;
     int K;
@@ -231,49 +239,92 @@ struct StridedLoaderK {
 // of a [T, ld] matrix (the token that sits in that expert row), optionally
 // scaled by row_w[row0+k] and rounded to bf16 once (dO = gate * dY).
 // src = matrix base + byte offset of the first element of this thread's chunk.
+//
+// The tokens and gates of a stage's 64 rows are the same for every thread that
+// loads from those rows, and a vector-memory instruction per row and thread
+// costs more issue time than the data loads themselves.  So one wave fetches
+// them (one row per lane, two stages ahead of their use) and hands them to the
+// workgroup through a ring of kIdxRing stages in LDS, from which every thread
+// reads its KR consecutive entries with one LDS read per array.
+// Protocol: prime() fills ring slots 0..3 with stages 0..3 (threads 0..255, one
+// stage per 64 threads) and leaves stage 4 in the first wave's registers; the
+// caller then runs a workgroup barrier.  gload_part(s, 0) with s >= 2, which the
+// main loop calls once per stage ahead of that stage's barrier, writes the held
+// stage to its slot and fetches the next one; the entries a thread reads for
+// stage s were therefore written at least two barriers earlier.  Row indices are
+// clamped to the expert's last row, so stages past the end stay readable.
+constexpr int kIdxRing = 8;
+constexpr int kIdxRingBytes = kIdxRing * BK * 8;   // tokens (int32) then gates (fp32)
+
 template <int NT, int NCH, bool SCALE>
 struct GatherStridedLoader {
     typedef TrGeom<NT, NCH> TG;
-    static constexpr bool kSpread = false;   // the whole stage moves in one go (part 0)
+    static_assert(TG::KR % 4 == 0, "the index ring is read four entries at a time");
+    static constexpr bool kNeedsPrime = true;
     const char* src;
     size_t ld_bytes;
     const int32_t* row_tok;
     const float* row_w;
     int row0, K;
+    char* ring;        // LDS, kIdxRingBytes
     u32x4_t reg[TG::KR];
     float sc[TG::KR];
-    // token ids (and gates) of the stage after the one in flight, fetched one stage early so
-    // that the data loads never wait on the index loads
-    int32_t tok_next[TG::KR];
-    float sc_next[TG::KR];
-    int next_stage;
+    int32_t held_tok;  // first wave: entry `lane` of stage held_stage
+    float held_w;
+    int held_stage;
     int lds_off, k0;
 
     __device__ __forceinline__ void init() {
         lds_off = TG::lds_off();
         k0 = TG::k0();
-        next_stage = -1;
     }
-    __device__ __forceinline__ void fetch_index(int s) {
-#pragma unroll
-        for (int r = 0; r < TG::KR; ++r) {
-            const int row = row0 + min(s * BK + k0 + r, K - 1);
-            tok_next[r] = row_tok[row];
-            if (SCALE) sc_next[r] = row_w[row];
+    __device__ __forceinline__ int32_t* ring_tok(int s) const {
+        return (int32_t*)(ring + (s & (kIdxRing - 1)) * BK * 4);
+    }
+    __device__ __forceinline__ float* ring_w(int s) const {
+        return (float*)(ring + kIdxRing * BK * 4 + (s & (kIdxRing - 1)) * BK * 4);
+    }
+    __device__ __forceinline__ void fetch_held(int s) {   // first wave only
+        const int row = row0 + min(s * BK + (int)(threadIdx.x & 63), K - 1);
+        held_tok = row_tok[row];
+        if (SCALE) held_w = row_w[row];
+        held_stage = s;
+    }
+    __device__ __forceinline__ void prime() {
+        const int tid = threadIdx.x;
+        if (tid < 256) {
+            const int s = tid >> 6, l = tid & 63;
+            const int row = row0 + min(s * BK + l, K - 1);
+            ring_tok(s)[l] = row_tok[row];
+            if (SCALE) ring_w(s)[l] = row_w[row];
         }
-        next_stage = s;
+        if (tid < 64) fetch_held(4);
     }
     __device__ __forceinline__ void gload_part(int s, int part) {
         if (part != 0) return;
-        if (next_stage != s) fetch_index(s);   // first stage of a tile (uniform branch)
+        if (s >= 2 && threadIdx.x < 64) {   // wave-uniform
+            ring_tok(held_stage)[threadIdx.x] = held_tok;
+            if (SCALE) ring_w(held_stage)[threadIdx.x] = held_w;
+            fetch_held(held_stage + 1);
+        }
+        int32_t tok[TG::KR];
+#pragma unroll
+        for (int r = 0; r < TG::KR; r += 4) {
+            const u32x4_t t4 = *(const u32x4_t*)(ring_tok(s) + k0 + r);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) tok[r + q] = (int32_t)t4[q];
+            if (SCALE) {
+                const u32x4_t w4 = *(const u32x4_t*)(ring_w(s) + k0 + r);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) sc[r + q] = __uint_as_float(w4[q]);
+            }
+        }
 #pragma unroll
         for (int r = 0; r < TG::KR; ++r) {
             const int k = s * BK + k0 + r;
-            if (SCALE) sc[r] = sc_next[r];
-            const u32x4_t v = *(const u32x4_t*)(src + (size_t)tok_next[r] * ld_bytes);
+            const u32x4_t v = *(const u32x4_t*)(src + (size_t)tok[r] * ld_bytes);
             reg[r] = (k < K) ? v : zero4();
         }
-        fetch_index(s + 1);   // row index is clamped inside: reads stay within the expert's rows
     }
     __device__ __forceinline__ void sstore_part(char* base, int part) {
         if (part != 0) return;
@@ -321,6 +372,9 @@ __device__ __forceinline__ void mma_mainloop(AL& al, BL& bl, int nk, char* smem,
     if (nk <= 0) return;   // empty reduction (an expert without rows): the tile is all zeros
     // wave-uniform, so the branch below is a scalar branch
     const bool active_u = __builtin_amdgcn_readfirstlane((int)active) != 0;
+    al.prime();
+    bl.prime();
+    if (AL::kNeedsPrime || BL::kNeedsPrime) __syncthreads();
 
 #pragma unroll
     for (int part = 0; part < 4; ++part) {
