@@ -13,6 +13,7 @@ workload has a backward).  Prints ONE JSON line:
   cpu_baseline  the CPU oracle timed on a bounded sample of the same workload
 
 Usage: python bench.py [--gpus 1] [--steps K] [--warmup W] [--config N]
+       python bench.py --model-shapes all [--tokens 8192] [--ep 8]   (sweep, one line per shape)
 """
 from __future__ import annotations
 
@@ -44,6 +45,13 @@ def parse():
     ap.add_argument("--no-backward", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    ap.add_argument("--model-shapes", type=str, default="",
+                    help="sweep instead of the contract line: comma-separated ids 1..12 of the "
+                         "paper's model-shape table (or 'all'); one JSON line per shape")
+    ap.add_argument("--tokens", type=int, default=8192, help="sweep: tokens (per rank)")
+    ap.add_argument("--ep", type=int, default=1,
+                    help="sweep: 1 = all experts local; W = one rank's share of W-way expert "
+                         "parallelism (W*tokens resident tokens, N_exp/W local experts)")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="also launch the plain copy kernel on this many MiB, 5 times "
                          "(scale for the HBM byte counters of a rocprofv3 --pmc run)")
@@ -116,12 +124,75 @@ def cpu_baseline(cfg, inp, has_bwd, budget_s):
     }
 
 
+def sweep_model_shapes(args):
+    """Forward and backward MegaKernel timings over the paper's model-shape table (synthetic
+    inputs drawn on the device).  One JSON line per shape; not the contract line."""
+    import torch
+    import moe_synth
+    import paper_2604_19241_amd as moe
+    ids = list(moe_synth.MODEL_SHAPES) if args.model_shapes == "all" else \
+        [int(v) for v in args.model_shapes.split(",")]
+    opts = moe.make_opts(schedule=args.schedule, tile_rows=args.tile_rows, workers=args.workers)
+    for mid in ids:
+        cfg = moe_synth.model_config(mid, tokens=args.tokens, ep=args.ep)
+        shape = moe.make_shape(**cfg.shape_dict())
+        sizes = moe.moe_workspace_bytes(shape)
+        dev = moe_synth.make_inputs_device(cfg, "cuda")
+        ws = {k: torch.empty(sizes[k], dtype=torch.uint8, device="cuda") for k in ("route", "fwd", "bwd")}
+        saved = moe.alloc_saved(shape, "cuda")
+        y = torch.empty((cfg.T, cfg.d), dtype=torch.bfloat16, device="cuda")
+        state, grads = {}, {}
+
+        def route():
+            state["r"] = moe.moe_route(shape, dev["logits"], ws=ws["route"])
+
+        def fwd():
+            moe.moe_fused_forward(shape, dev["x"], dev["w_gate"], dev["w_up"], dev["w_down"],
+                                  state["r"], y=y, saved=saved, ws=ws["fwd"], opts=opts)
+
+        def bwd():
+            grads["out"] = moe.moe_fused_backward(shape, dev["dy"], dev["x"], dev["w_gate"],
+                                                  dev["w_up"], dev["w_down"], state["r"], saved,
+                                                  ws=ws["bwd"], opts=opts, out=grads.get("out"))
+
+        route()
+        t_end = time.perf_counter() + 0.4          # clocks ramp up under load
+        while time.perf_counter() < t_end:
+            fwd()
+            bwd()
+            torch.cuda.synchronize()
+        assert moe.moe_device_status(ws["fwd"]) == 0 and moe.moe_device_status(ws["bwd"]) == 0
+        n = max(5, min(args.steps, 30))
+        ms_r, ms_f, ms_b = event_ms(route, n), event_ms(fwd, n), event_ms(bwd, n)
+        A = int(state["r"].offsets[-1].item())
+        f_fwd = 6.0 * A * cfg.d * cfg.I
+        counts = state["r"].counts.cpu().tolist()
+        print(json.dumps({
+            "sweep": "model-shapes", "id": mid, "workload": cfg.name, "T": cfg.T, "d": cfg.d,
+            "I": cfg.I, "E": cfg.E, "k": cfg.k, "local_experts": cfg.e_count, "routed_rows": A,
+            "rows_per_expert_mean": A / cfg.e_count, "rows_per_expert_max": max(counts),
+            "route_ms": ms_r[1], "forward_ms": ms_f[1], "backward_ms": ms_b[1],
+            "forward_tflops": f_fwd / (ms_f[1] * 1e-3) / 1e12,
+            "backward_tflops": 2 * f_fwd / (ms_b[1] * 1e-3) / 1e12,
+            "step_tflops": 3 * f_fwd / ((ms_r[1] + ms_f[1] + ms_b[1]) * 1e-3) / 1e12,
+            "dtype": "bf16", "data": "synthetic (drawn on the device)", "timing": "median of HIP events",
+        }), flush=True)
+        del dev, ws, saved, y, grads, state
+        torch.cuda.empty_cache()
+
+
 def main():
     args = parse()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
               "use --gpus 1", file=sys.stderr)
         sys.exit(2)
+    if args.model_shapes:
+        import torch
+        assert torch.cuda.is_available(), "bench.py needs an MI355X"
+        torch.cuda.set_device(0)
+        sweep_model_shapes(args)
+        return
     import torch
     import moe_synth
     import paper_2604_19241_amd as moe

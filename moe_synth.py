@@ -57,6 +57,42 @@ CONFIGS = {
 }
 
 
+# The twelve layer shapes of the paper's Table "MoE Model Configurations Evaluated":
+# id -> (model name, H_dim, H_inter, N_exp, top-k).
+MODEL_SHAPES = {
+    1: ("DeepSeek-MoE-16B", 2048, 1408, 64, 6),
+    2: ("DeepSeek-OCR-2", 1280, 896, 64, 6),
+    3: ("DeepSeek-V2-Lite", 2048, 1408, 64, 6),
+    4: ("DeepSeek-V2-Chat", 5120, 1536, 160, 6),
+    5: ("DeepSeek-R1", 7168, 2048, 256, 8),
+    6: ("Qwen3-30B-A3B", 2048, 768, 128, 8),
+    7: ("Qwen3-235B-A22B", 4096, 1536, 128, 8),
+    8: ("Qwen3-Coder-480B", 6144, 2560, 160, 8),
+    9: ("Qwen3-Next-80B", 2048, 512, 512, 10),
+    10: ("Qwen3-Omni-30B", 1024, 384, 128, 6),
+    11: ("Kimi-K2", 7168, 2048, 384, 8),
+    12: ("Kimi-Linear-48B", 2304, 1024, 256, 8),
+}
+
+
+def model_config(mid: int, tokens: int = 8192, ep: int = 1, e_start: int | None = None,
+                 e_count: int | None = None) -> MoEConfig:
+    """Layer shape MoE-<mid> of the paper's model table as a one-GPU workload.
+
+    ep = 1: `tokens` tokens, every expert local.  ep = W > 1: one rank's share of W-way
+    expert parallelism at `tokens` tokens per rank: the W*tokens tokens of all ranks are
+    resident, the first N_exp/W experts are local, so about tokens*k rows are routed here
+    (the paper's evaluation setting, Section 6.1, without the token exchange).
+    e_start/e_count override the local expert range (smaller shares for parity tests)."""
+    name, d, inter, n_exp, k = MODEL_SHAPES[mid]
+    assert n_exp % ep == 0
+    if e_count is None:
+        e_count = n_exp // ep
+    return MoEConfig(f"moe-{mid}-{name.lower()}" + (f"-ep{ep}" if ep > 1 else ""),
+                     T=tokens * ep, d=d, E=n_exp, k=k, I=inter,
+                     e_start=0 if e_start is None else e_start, e_count=e_count, backward=True)
+
+
 def _gen(seed: int) -> torch.Generator:
     g = torch.Generator(device="cpu")
     g.manual_seed(seed)
@@ -121,6 +157,37 @@ def make_inputs(cfg: MoEConfig, seed: int | None = None, with_dy: bool | None = 
         out["w_gate"] = _normal_bf16((cfg.e_count, cfg.d, cfg.I), 0.02, g)
         out["w_up"] = _normal_bf16((cfg.e_count, cfg.d, cfg.I), 0.02, g)
         out["w_down"] = _normal_bf16((cfg.e_count, cfg.I, cfg.d), 0.02, g)
+    return out
+
+
+def make_inputs_device(cfg: MoEConfig, device, seed: int | None = None, with_dy: bool = True) -> dict:
+    """The same tensors drawn directly on `device` (timing sweeps over large shapes, where
+    drawing tens of GB on the host would take minutes).  Same distributions as make_inputs,
+    a different random stream, logits as a plain fp32 product: parity tests never use these."""
+    g = torch.Generator(device=device)
+    g.manual_seed(BASE_SEED if seed is None else seed)
+
+    def normal(shape, std):
+        out = torch.empty(shape, dtype=torch.bfloat16, device=device)
+        lead = shape[0]
+        step = max(1, (1 << 28) // max(out.numel() // max(lead, 1), 1))
+        for i in range(0, lead, step):
+            j = min(lead, i + step)
+            out[i:j] = (torch.randn((j - i,) + tuple(shape[1:]), generator=g, device=device,
+                                    dtype=torch.float32) * std).to(torch.bfloat16)
+        return out
+
+    out = {"x": normal((cfg.T, cfg.d), 1.0)}
+    w_r = normal((cfg.d, cfg.E), 0.02)
+    logits = out["x"].float() @ w_r.float()
+    if cfg.zipf_s > 0:
+        logits = logits + zipf_bias(cfg.E, cfg.zipf_s, _gen(BASE_SEED))[None, :].to(device)
+    out["logits"] = logits.contiguous()
+    if with_dy:
+        out["dy"] = normal((cfg.T, cfg.d), 1.0)
+    out["w_gate"] = normal((cfg.e_count, cfg.d, cfg.I), 0.02)
+    out["w_up"] = normal((cfg.e_count, cfg.d, cfg.I), 0.02)
+    out["w_down"] = normal((cfg.e_count, cfg.I, cfg.d), 0.02)
     return out
 
 
