@@ -264,6 +264,13 @@ def main():
     ms_route = event_ms(route, n)
     ms_fwd = event_ms(fwd, n)
     ms_bwd = event_ms(bwd, n) if has_bwd else None
+    # not part of the step on one GPU: the W > 1 index stage (Algorithm 1, lines 3-14) for one
+    # rank of 8, with the realised histogram standing in for every rank's
+    ms_gmap = None
+    if cfg.e_count == cfg.E and cfg.E % 8 == 0:
+        c_all = torch.stack([state["r"].counts] * 8).contiguous()
+        ws_g = torch.empty(8 * cfg.E, dtype=torch.uint8, device="cuda")
+        ms_gmap = event_ms(lambda: moe.moe_global_map(shape, 8, 3, state["r"], c_all, ws=ws_g), n)
     # the same with cold caches: a 512 MiB streaming copy ahead of every call evicts the weights,
     # activations and routing tables from the L2s and the 256 MB Infinity Cache
     flush_src = torch.zeros(512 << 20, dtype=torch.uint8, device="cuda")
@@ -320,6 +327,7 @@ def main():
         "pct_of_bf16_mfma_peak": 100.0 * value / MFMA_BF16_PEAK_TFLOPS,
         "phases_ms": {"route": ms_route[0], "forward": ms_fwd[0],
                       "backward": ms_bwd[0] if ms_bwd else None},
+        "global_map_w8_ms": ms_gmap[1] if ms_gmap else None,
         "phases_ms_median_min": {"route": ms_route[1:], "forward": ms_fwd[1:],
                                  "backward": ms_bwd[1:] if ms_bwd else None},
         "phases_ms_cold_caches": {"forward": cold_fwd[0], "backward": cold_bwd[0] if cold_bwd else None},

@@ -157,6 +157,43 @@ int moe_fused_backward(const moe_shape_t* shape, const void* dy, const void* x,
 int moe_route_backward(const moe_shape_t* shape, const int32_t* topk_idx, const float* topk_w,
                        const float* dtopk_w, float* dlogits, void* stream);
 
+/* Outputs of moe_global_map (device pointers, all written by the call). */
+typedef struct {
+    int32_t* dst_rank;     /* [T,k]  r_tgt = e / N_epr */
+    int32_t* dst_expert;   /* [T,k]  e_loc = e % N_epr */
+    int32_t* dst_off;      /* [T,k]  final_idx: position inside the expert's segment */
+    int32_t* dst_row;      /* [T,k]  row of the destination rank's buffer: segment start + final_idx */
+    int32_t* send;         /* [T,k]  1 = first slot of its token for that rank (the copy that
+                                     crosses the link), 0 = replicated at the destination */
+    int32_t* n_dst_ranks;  /* [T]    distinct destination ranks of the token */
+    int32_t* recv_offsets; /* [E/W + 1]  this rank as destination: start of each local expert's
+                                     segment, and the total rows it receives */
+} moe_global_map_t;
+
+/* Deterministic global token mapping for one rank of W (Section 3.1, Algorithm 1
+ * lines 3-14 and Eq. 1), the part of the W > 1 index stage that runs on one
+ * GPU; the AllGather of the histograms is the caller's and arrives as c_all.
+ * With N_epr = E / W experts per rank, slot (t,j) with expert e goes to rank
+ * e / N_epr, local expert e % N_epr, at
+ *   final_idx = M_loc[t,j] - O_exp[e] + sum_{r' < rank} c_all[r', e]
+ * inside that expert's segment; segments of a rank's experts follow each other
+ * without padding, each as long as the column sum of c_all, so
+ *   dst_row = sum_{e' in the rank, e' < e} sum_r c_all[r, e'] + final_idx.
+ * Rows of one expert end up ordered by (source rank, token, slot): the stable
+ * sort of the rank-concatenated tokens, with no atomics.
+ *   shape    T, E, k are used; e_start must be 0 and e_count = E (the routing
+ *            must rank all experts: M_loc = routing->inv_perm, O_exp =
+ *            routing->offsets); E % W == 0, 1 <= W <= 64, 0 <= rank < W
+ *            (MOE_ERR_SHAPE otherwise)
+ *   routing  what moe_route wrote for this rank's tokens (topk_idx, inv_perm,
+ *            offsets are read)
+ *   c_all    [W,E] int32, device: row r = rank r's counts; row `rank` must equal
+ *            routing->counts (not checked)
+ *   ws       8*E bytes of device scratch */
+int moe_global_map(const moe_shape_t* shape, int32_t W, int32_t rank, const moe_routing_t* routing,
+                   const int32_t* c_all, const moe_global_map_t* out, void* ws, size_t ws_bytes,
+                   void* stream);
+
 /* Synchronises `stream`, reads the status word a forward/backward call left in
  * its workspace and returns MOE_OK or MOE_ERR_DEVICE (test and debug aid; the
  * hot path never calls it). */

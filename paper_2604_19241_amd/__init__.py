@@ -4,7 +4,8 @@ The hot path lives in libuniep_moe.so (hand-written HIP for gfx950); this
 package only marshals arguments.  See include/uniep_moe.h for the contract.
 """
 from .binding import (  # noqa: F401
-    MoEError, MoEOpts, MoEShape, Routing, alloc_saved, load_library, make_opts, make_shape,
-    moe_calibration_copy, moe_device_status, moe_fused_backward, moe_fused_forward, moe_route, moe_route_backward, moe_saved_layout,
-    moe_workspace_bytes, saved_views, status_string,
+    GlobalMap, MoEError, MoEOpts, MoEShape, Routing, alloc_saved, load_library, make_opts,
+    make_shape, moe_calibration_copy, moe_device_status, moe_fused_backward, moe_fused_forward,
+    moe_global_map, moe_route, moe_route_backward, moe_saved_layout, moe_workspace_bytes,
+    saved_views, status_string,
 )

@@ -20,8 +20,8 @@ MOE_OK = 0
 MOE_ERR_ARG, MOE_ERR_SHAPE, MOE_ERR_WORKSPACE, MOE_ERR_HIP, MOE_ERR_DEVICE = -1, -2, -3, -4, -5
 
 EXPORTS = ("moe_workspace_bytes", "moe_saved_layout", "moe_route", "moe_fused_forward",
-           "moe_fused_backward", "moe_route_backward", "moe_device_status", "moe_status_string",
-           "moe_calibration_copy")
+           "moe_fused_backward", "moe_route_backward", "moe_global_map", "moe_device_status",
+           "moe_status_string", "moe_calibration_copy")
 
 
 class MoEShape(ctypes.Structure):
@@ -205,6 +205,52 @@ def moe_route_backward(shape: MoEShape, routing: "Routing", dtopk_w: torch.Tenso
     _check(lib.moe_route_backward(ctypes.byref(shape), _ptr(routing.topk_idx), _ptr(routing.topk_w),
                                   _ptr(dtopk_w), _ptr(out), _stream(dev)), "moe_route_backward")
     return out
+
+
+class MoEGlobalMapC(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in
+                ("dst_rank", "dst_expert", "dst_off", "dst_row", "send", "n_dst_ranks",
+                 "recv_offsets")]
+
+
+@dataclass
+class GlobalMap:
+    dst_rank: torch.Tensor      # [T,k] i32
+    dst_expert: torch.Tensor    # [T,k] i32
+    dst_off: torch.Tensor       # [T,k] i32
+    dst_row: torch.Tensor       # [T,k] i32
+    send: torch.Tensor          # [T,k] i32
+    n_dst_ranks: torch.Tensor   # [T] i32
+    recv_offsets: torch.Tensor  # [E/W + 1] i32
+
+
+def moe_global_map(shape: MoEShape, W: int, rank: int, routing: "Routing", c_all: torch.Tensor,
+                   ws: Optional[torch.Tensor] = None) -> GlobalMap:
+    """Destination (rank, local expert, offset, row) of every slot of this rank's tokens, from
+    the all-gathered histograms c_all [W,E] int32 (device)."""
+    dev = c_all.device
+    assert c_all.is_cuda and c_all.dtype == torch.int32 and c_all.is_contiguous()
+    assert tuple(c_all.shape) == (W, shape.E)
+    T, k = shape.T, shape.k
+
+    def i32(*size):
+        return torch.empty(size, dtype=torch.int32, device=dev)
+
+    g = GlobalMap(i32(T, k), i32(T, k), i32(T, k), i32(T, k), i32(T, k), i32(T),
+                  i32(shape.E // max(W, 1) + 1))
+    if ws is None:
+        ws = _ws(8 * shape.E, dev)
+    cs = routing.c_struct()
+    gs = MoEGlobalMapC(*(t.data_ptr() for t in (g.dst_rank, g.dst_expert, g.dst_off, g.dst_row,
+                                                g.send, g.n_dst_ranks, g.recv_offsets)))
+    lib = load_library()
+    lib.moe_global_map.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p,
+                                   ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                   ctypes.c_size_t, ctypes.c_void_p]
+    _check(lib.moe_global_map(ctypes.byref(shape), int(W), int(rank), ctypes.byref(cs), _ptr(c_all),
+                              ctypes.byref(gs), _ptr(ws), ctypes.c_size_t(ws.numel()),
+                              _stream(dev)), "moe_global_map")
+    return g
 
 
 def moe_device_status(ws: torch.Tensor) -> int:

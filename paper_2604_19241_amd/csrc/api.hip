@@ -10,6 +10,8 @@ int route_backward_launch(const moe_shape_t& s, const int32_t* topk_idx, const f
                           const float* dtopk_w, float* dlogits, hipStream_t st);
 int route_launch(const moe_shape_t& s, const float* logits, const moe_routing_t& out, void* ws,
                  hipStream_t st);
+int global_map_launch(const moe_shape_t& s, int W, int rank, const moe_routing_t& r,
+                      const int32_t* c_all, const moe_global_map_t& out, void* ws, hipStream_t st);
 size_t fwd_workspace_bytes(const moe_shape_t& s);
 size_t fwd_ctrl_bytes(const moe_shape_t& s);
 int fwd_launch(const moe_shape_t& s, const void* x, const void* w_gate, const void* w_up,
@@ -213,6 +215,28 @@ int moe_route_backward(const moe_shape_t* shape, const int32_t* topk_idx, const 
     if (!aligned(topk_idx, 4) || !aligned(topk_w, 4) || !aligned(dtopk_w, 4) || !aligned(dlogits, 4))
         return MOE_ERR_ARG;
     return route_backward_launch(*shape, topk_idx, topk_w, dtopk_w, dlogits, (hipStream_t)stream);
+}
+
+int moe_global_map(const moe_shape_t* shape, int32_t W, int32_t rank, const moe_routing_t* routing,
+                   const int32_t* c_all, const moe_global_map_t* out, void* ws, size_t ws_bytes,
+                   void* stream) {
+    int rc = check_shape(shape);
+    if (rc != MOE_OK) return rc;
+    if (shape->e_start != 0 || shape->e_count != shape->E) return MOE_ERR_SHAPE;
+    if (W < 1 || W > 64 || shape->E % W != 0 || rank < 0 || rank >= W) return MOE_ERR_SHAPE;
+    if (!routing || !out || !c_all || !ws) return MOE_ERR_ARG;
+    if (!routing->offsets || !out->recv_offsets) return MOE_ERR_ARG;
+    if (shape->T > 0 && (!routing->topk_idx || !routing->inv_perm || !out->dst_rank ||
+                         !out->dst_expert || !out->dst_off || !out->dst_row || !out->send ||
+                         !out->n_dst_ranks))
+        return MOE_ERR_ARG;
+    const void* ptrs[] = {routing->topk_idx, routing->inv_perm, routing->offsets, c_all,
+                          out->dst_rank, out->dst_expert, out->dst_off, out->dst_row, out->send,
+                          out->n_dst_ranks, out->recv_offsets, ws};
+    for (const void* q : ptrs)
+        if (!aligned(q, 4)) return MOE_ERR_ARG;
+    if (ws_bytes < (size_t)shape->E * 8) return MOE_ERR_WORKSPACE;
+    return global_map_launch(*shape, W, rank, *routing, c_all, *out, ws, (hipStream_t)stream);
 }
 
 int moe_device_status(const void* ws, void* stream) {

@@ -247,7 +247,98 @@ route_backward_kernel(const int32_t* __restrict__ topk_idx, const float* __restr
     }
 }
 
+// ------------------------------------------------------------------ global mapping, W > 1
+// Algorithm 1 for one rank of W (Section 3.1).  The AllGather of the per-rank
+// histograms is the caller's; c_all [W, E] is its result.
+
+// One workgroup of 1024 threads, thread e per expert.  Eq. 1 along the rank axis,
+// the total rows every expert receives, and the start of every expert's segment
+// in its destination rank's buffer (exclusive scan inside each group of n_epr
+// experts).  Writes off_base[e] = O_all[rank, e] - O_exp[e] and row_base[e] =
+// segment start + off_base[e], so that the mapping kernel only adds M_loc, and
+// this rank's own segment table recv_offsets [n_epr + 1].
+__global__ void __launch_bounds__(1024)
+global_offsets_kernel(const int32_t* __restrict__ c_all, const int32_t* __restrict__ o_exp, int E,
+                      int W, int rank, int n_epr, int32_t* __restrict__ off_base,
+                      int32_t* __restrict__ row_base, int32_t* __restrict__ recv_offsets) {
+    __shared__ int32_t s_scan[1024];
+    const int e = threadIdx.x;
+    int total = 0, before = 0;
+    if (e < E) {
+        for (int r = 0; r < W; ++r) {
+            const int c = c_all[(size_t)r * E + e];
+            if (r < rank) before += c;
+            total += c;
+        }
+    }
+    s_scan[e] = total;
+    __syncthreads();
+    for (int off = 1; off < 1024; off <<= 1) {       // inclusive scan over all experts
+        const int add = (e >= off) ? s_scan[e - off] : 0;
+        __syncthreads();
+        s_scan[e] += add;
+        __syncthreads();
+    }
+    if (e < E) {
+        const int g0 = (e / n_epr) * n_epr;              // first expert of e's rank
+        const int start = (s_scan[e] - total) - (g0 > 0 ? s_scan[g0 - 1] : 0);
+        const int ob = before - o_exp[e];
+        off_base[e] = ob;
+        row_base[e] = start + ob;
+        if (e / n_epr == rank) {
+            recv_offsets[e - g0] = start;
+            if (e - g0 == n_epr - 1) recv_offsets[n_epr] = start + total;
+        }
+    }
+}
+
+// One thread per token: destination (rank, local expert, offset inside the expert's
+// segment, row of the destination buffer) of each of its k slots; `send` marks the first
+// slot, in slot order, that targets a rank (the copy that crosses the link; the relay
+// worker of Section 3.2 replicates it for the token's other experts on that rank).
+__global__ void __launch_bounds__(kRouteThreads)
+global_map_kernel(const int32_t* __restrict__ topk_idx, const int32_t* __restrict__ m_loc, int T,
+                  int k, int n_epr, const int32_t* __restrict__ off_base,
+                  const int32_t* __restrict__ row_base, int32_t* __restrict__ dst_rank,
+                  int32_t* __restrict__ dst_expert, int32_t* __restrict__ dst_off,
+                  int32_t* __restrict__ dst_row, int32_t* __restrict__ send,
+                  int32_t* __restrict__ n_dst_ranks) {
+    const int t = blockIdx.x * kRouteThreads + threadIdx.x;
+    if (t >= T) return;
+    unsigned long long seen = 0ull;
+    for (int j = 0; j < k; ++j) {
+        const size_t f = (size_t)t * k + j;
+        const int e = topk_idx[f];
+        const int r_tgt = e / n_epr;
+        const int loc = m_loc[f];
+        dst_rank[f] = r_tgt;
+        dst_expert[f] = e - r_tgt * n_epr;
+        dst_off[f] = loc + off_base[e];
+        dst_row[f] = loc + row_base[e];
+        const unsigned long long bit = 1ull << r_tgt;
+        send[f] = (seen & bit) ? 0 : 1;
+        seen |= bit;
+    }
+    n_dst_ranks[t] = __popcll(seen);
+}
+
 // ------------------------------------------------------------------ host side
+
+int global_map_launch(const moe_shape_t& s, int W, int rank, const moe_routing_t& r,
+                      const int32_t* c_all, const moe_global_map_t& out, void* ws, hipStream_t st) {
+    int32_t* off_base = (int32_t*)ws;
+    int32_t* row_base = off_base + s.E;
+    const int n_epr = s.E / W;
+    hipLaunchKernelGGL(global_offsets_kernel, dim3(1), dim3(1024), 0, st, c_all, r.offsets, s.E, W,
+                       rank, n_epr, off_base, row_base, out.recv_offsets);
+    if (s.T > 0)
+        hipLaunchKernelGGL(global_map_kernel, dim3((s.T + kRouteThreads - 1) / kRouteThreads),
+                           dim3(kRouteThreads), 0, st, r.topk_idx, r.inv_perm, s.T, s.k, n_epr,
+                           off_base, row_base, out.dst_rank, out.dst_expert, out.dst_off,
+                           out.dst_row, out.send, out.n_dst_ranks);
+    return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
+}
+
 
 int route_backward_launch(const moe_shape_t& s, const int32_t* topk_idx, const float* topk_w,
                           const float* dtopk_w, float* dlogits, hipStream_t st) {

@@ -23,7 +23,7 @@ def test_every_declared_symbol_is_exported(lib):
     names = set(re.findall(r"^(?:int|const char\*)\s+(moe_\w+)\s*\(", header, flags=re.M))
     assert {"moe_route", "moe_fused_forward", "moe_fused_backward", "moe_route_backward",
             "moe_workspace_bytes", "moe_saved_layout", "moe_device_status", "moe_status_string",
-            "moe_calibration_copy"} <= names
+            "moe_calibration_copy", "moe_global_map"} <= names
     for n in names:
         assert hasattr(lib, n), n
 
@@ -40,6 +40,7 @@ def test_struct_sizes_match_header(lib):
     assert ctypes.sizeof(b.MoEShape) == 28
     assert ctypes.sizeof(b.MoEOpts) == 32
     assert ctypes.sizeof(b.MoERoutingC) == 48
+    assert ctypes.sizeof(b.MoEGlobalMapC) == 56
 
 
 @pytest.mark.parametrize("kw", [
@@ -116,6 +117,35 @@ def test_calibration_copy_rejects_bad_arguments(lib):
     assert lib.moe_calibration_copy(256, 264, 256, None) == b.MOE_ERR_ARG        # misaligned source
     assert lib.moe_calibration_copy(256, 512, 100, None) == b.MOE_ERR_ARG        # size not a multiple of 16
     assert lib.moe_calibration_copy(256, 512, 0, None) == b.MOE_OK               # nothing to copy, nothing launched
+
+
+def test_global_map_rejects_bad_arguments(lib):
+    from paper_2604_19241_amd import binding as b
+    lib.moe_global_map.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p,
+                                   ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                   ctypes.c_size_t, ctypes.c_void_p]
+    fake = 0x1000
+    r = b.MoERoutingC(*([fake] * 6))
+    g = b.MoEGlobalMapC(*([fake] * 7))
+
+    def call(s, W=4, rank=1, routing=r, c_all=fake, out=g, ws=fake, nbytes=1 << 20):
+        return lib.moe_global_map(ctypes.byref(s), W, rank, ctypes.byref(routing) if routing else None,
+                                  c_all, ctypes.byref(out) if out else None, ws, nbytes, None)
+
+    ok = b.make_shape(T=8, d=64, E=8, k=2, I=64)
+    assert call(b.make_shape(T=8, d=64, E=8, k=2, I=64, e_start=0, e_count=4)) == b.MOE_ERR_SHAPE
+    assert call(ok, W=3) == b.MOE_ERR_SHAPE            # E not a multiple of W
+    assert call(ok, W=0) == b.MOE_ERR_SHAPE
+    assert call(b.make_shape(T=8, d=64, E=128, k=2, I=64), W=128) == b.MOE_ERR_SHAPE   # W > 64
+    assert call(ok, rank=4) == b.MOE_ERR_SHAPE
+    assert call(ok, rank=-1) == b.MOE_ERR_SHAPE
+    assert call(ok, c_all=None) == b.MOE_ERR_ARG
+    assert call(ok, routing=None) == b.MOE_ERR_ARG
+    assert call(ok, out=None) == b.MOE_ERR_ARG
+    assert call(ok, ws=None) == b.MOE_ERR_ARG
+    assert call(ok, c_all=0x1002) == b.MOE_ERR_ARG     # misaligned
+    assert call(ok, out=b.MoEGlobalMapC(*([fake] * 5 + [0, fake]))) == b.MOE_ERR_ARG
+    assert call(ok, nbytes=63) == b.MOE_ERR_WORKSPACE  # needs 8 * E bytes
 
 
 def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
