@@ -284,8 +284,8 @@ def main():
     cold_bwd = event_ms(bwd, nc, before=flush) if has_bwd else None
     del flush_src, flush_dst
     fwd_tflops = f_fwd / (ms_fwd[0] * 1e-3) / 1e12
-    # waves per workgroup the library picks (tile height 32 * nw): 8 from 160 rows per expert up
-    nw = {128: 4, 256: 8}.get(args.tile_rows, 8 if cfg.T * cfg.k / cfg.E >= 160.0 else 4)
+    # waves per workgroup (tile height 32 * nw): 8 unless 128-row tiles are asked for
+    nw = 4 if args.tile_rows == 128 else 8
 
     def roof(kernel, what, flops, ms):
         tf = flops / (ms[0] * 1e-3) / 1e12

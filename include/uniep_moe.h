@@ -83,7 +83,7 @@ typedef struct {
                          can be co-resident: the deadlock-freedom condition of Section 3.1) */
     int32_t spin_limit_ms; /* bound on every scoreboard wait; 0 = 2000 ms.  A wait that
                               exceeds it sets MOE_ERR_DEVICE in the workspace and drains */
-    int32_t tile_rows;     /* rows per GEMM row tile: 0 = chosen from the shape, or 128 / 256 */
+    int32_t tile_rows;     /* rows per GEMM row tile: 0 = default (256), or 128 / 256 */
     int32_t reserved[4];   /* must be 0 */
 } moe_opts_t;
 

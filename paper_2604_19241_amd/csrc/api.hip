@@ -61,14 +61,11 @@ int check_opts(const moe_opts_t* o, moe_opts_t* out) {
     return MOE_OK;
 }
 
-// Waves per workgroup = row-tile height / 32: 256-row tiles (8 waves, two per
-// SIMD) unless the experts are small.
-int pick_nw(const moe_shape_t& s, const moe_opts_t& o) {
-    if (o.tile_rows == 128) return 4;
-    if (o.tile_rows == 256) return 8;
-    const double avg = (double)s.T * s.k / s.E;
-    return avg >= 160.0 ? 8 : 4;
-}
+// Waves per workgroup = row-tile height / 32.  256-row tiles (8 waves, two per
+// SIMD) by default at every size: waves whose rows lie outside a tile skip the
+// matrix work, and measured from 20 to 6000 rows per expert the 8-wave tiles
+// are 1.3-2x faster than the 4-wave ones.
+int pick_nw(const moe_shape_t&, const moe_opts_t& o) { return o.tile_rows == 128 ? 4 : 8; }
 
 struct SavedLayout {
     size_t gu, h, o, total;

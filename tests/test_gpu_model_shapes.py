@@ -16,30 +16,31 @@ from test_gpu_forward import MAX_ABS, REL_L2
 
 pytestmark = pytest.mark.gpu
 
-# (model id, tokens, e_start, e_count); tokens*k/N_exp >= 160 selects the 8-wave tiles,
-# fewer rows per expert the 4-wave tiles
+# (model id, tokens, e_start, e_count, tile_rows); tile_rows 0 = the default 256-row tiles
 CASES = [
-    (1, 2048, 8, 8),      # I = 1408: 5.5 column tiles of 256
-    (2, 2048, 8, 16),     # d = 1280, I = 896, k = 6
-    (4, 8192, 40, 4),     # d = 5120, 160 experts
-    (7, 4096, 0, 4),      # d = 4096, I = 1536
-    (8, 1024, 158, 2),    # d = 6144, I = 2560, the last two experts, ~50 rows each
-    (9, 8192, 100, 16),   # 512 experts, k = 10, I = 512
-    (10, 4096, 96, 32),   # I = 384
-    (10, 1024, 0, 128),   # every expert local, ~50 rows each
-    (12, 8192, 32, 8),    # d = 2304
+    (1, 2048, 8, 8, 0),      # I = 1408: 5.5 column tiles of 256
+    (2, 2048, 8, 16, 0),     # d = 1280, I = 896, k = 6
+    (4, 8192, 40, 4, 0),     # d = 5120, 160 experts
+    (7, 4096, 0, 4, 0),      # d = 4096, I = 1536
+    (8, 1024, 158, 2, 0),    # d = 6144, I = 2560, the last two experts, ~50 rows each
+    (8, 1024, 158, 2, 128),  # the same on 128-row tiles (4 waves)
+    (9, 8192, 100, 16, 0),   # 512 experts, k = 10, I = 512
+    (10, 4096, 96, 32, 0),   # I = 384
+    (10, 1024, 0, 128, 0),   # every expert local, ~50 rows each
+    (10, 1024, 0, 128, 128),
+    (12, 8192, 32, 8, 0),    # d = 2304
 ]
 
 
-@pytest.mark.parametrize("mid,tokens,e_start,e_count", CASES)
-def test_model_shape_forward_backward(mid, tokens, e_start, e_count):
+@pytest.mark.parametrize("mid,tokens,e_start,e_count,tile_rows", CASES)
+def test_model_shape_forward_backward(mid, tokens, e_start, e_count, tile_rows):
     cfg = moe_synth.model_config(mid, tokens=tokens, e_start=e_start, e_count=e_count)
-    say(f"[model shape] {cfg.name} {cfg.shape_dict()}")
+    say(f"[model shape] {cfg.name} {cfg.shape_dict()} tile_rows={tile_rows}")
     inp = moe_synth.make_inputs(cfg, seed=100 + mid, with_dy=True)
     b = bits(inp, ("x", "dy", "w_gate", "w_up", "w_down"))
     sh = cfg.shape_dict()
     r = oracle.route(sh, inp["logits"].numpy())
-    g, routing = gpu_fwd_bwd(cfg, inp, schedule=0, tile_rows=0)
+    g, routing = gpu_fwd_bwd(cfg, inp, schedule=0, tile_rows=tile_rows)
     got = gpu_routing_as_np(routing)
     for key in ("topk_idx", "counts", "offsets", "perm", "inv_perm"):
         assert np.array_equal(got[key], r[key]), key
@@ -48,7 +49,7 @@ def test_model_shape_forward_backward(mid, tokens, e_start, e_count):
     import paper_2604_19241_amd as moe
     shape = moe.make_shape(**sh)
     y = moe.moe_fused_forward(shape, inp["x"].cuda(), inp["w_gate"].cuda(), inp["w_up"].cuda(),
-                              inp["w_down"].cuda(), routing)
+                              inp["w_down"].cuda(), routing, opts=moe.make_opts(tile_rows=tile_rows))
     want = oracle.forward(sh, b["x"], b["w_gate"], b["w_up"], b["w_down"], r, round_bf16=True,
                           acc="f32")
     yg = to_f64(y)
