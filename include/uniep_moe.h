@@ -77,8 +77,11 @@ typedef struct {
 
 /* Launch options (host struct; NULL = all defaults). */
 typedef struct {
-    int32_t schedule; /* 0 = default (persistent), 1 = persistent work-queue megakernel,
-                         2 = staged: one launch per phase (same tile code; for profiling) */
+    int32_t schedule; /* 0 = default (= 3), 1 = one persistent work-queue MegaKernel for every
+                         task, 2 = staged: one launch per phase (same tile code; for profiling),
+                         3 = one persistent MegaKernel for all GEMM tasks with scoreboard
+                         waits, then a second launch of the same kernel for the tail tasks
+                         (combine / dX), which may only start once every GEMM task is done */
     int32_t workers;  /* persistent workgroups; 0 = one per resident slot (never more than
                          can be co-resident: the deadlock-freedom condition of Section 3.1) */
     int32_t spin_limit_ms; /* bound on every scoreboard wait; 0 = 2000 ms.  A wait that

@@ -447,13 +447,13 @@ bwd_worker_kernel(BwdParams p, int phase) {
     const int pass = phase < 0 ? 0 : 1 + phase;
     const int home = xcc_id();
     const bool use_lists = phase != B_DX;
-    const bool use_tail = phase < 0 || phase == B_DX;
+    const bool use_tail = phase == -1 || phase == B_DX;
     // this launch runs dXp tiles: its workers publish their rows once, when they run out of GEMM work
-    const bool publishes = phase < 0 || phase == B_DXP;
+    const bool publishes = phase == -1 || phase == B_DXP;
     bool arrived = false;
     unsigned exhausted = 0;
     if (threadIdx.x == 0) {
-        if (phase < 0) worker_started(ctrl, home);
+        if (phase == -1) worker_started(ctrl, home);
         s_task = fetch_task(ctrl, pass, home, exhausted, use_lists, use_tail);
     }
     __syncthreads();
@@ -525,6 +525,10 @@ bwd_worker_kernel(BwdParams p, int phase) {
         __syncthreads();
         if (threadIdx.x == 0) s_task = fetch_finish(pf, ctrl, pass, home, exhausted, use_lists, use_tail);
         __syncthreads();
+    }
+    if (phase == -2) {   // GEMM tasks only: the kernel boundary publishes the rows
+        if (threadIdx.x == 0) add_relaxed(ctrl + CTRL_DONE, 1);
+        return;
     }
     if (publishes && !arrived) {
         wait_stores();
@@ -611,6 +615,11 @@ static int bwd_launch_nw(BwdParams& p, const moe_opts_t& opts, hipStream_t st) {
         for (int phase = 0; phase < 5; ++phase)
             hipLaunchKernelGGL(bwd_worker_kernel<NW>, dim3(workers), dim3(Geom<NW>::NT),
                                Geom<NW>::SMEM + kIdxRingBytes, st, p, phase);
+    } else if (opts.schedule != 1) {   // 0 (default) and 3: GEMM MegaKernel, then the tail tasks
+        hipLaunchKernelGGL(bwd_worker_kernel<NW>, dim3(workers), dim3(Geom<NW>::NT),
+                           Geom<NW>::SMEM + kIdxRingBytes, st, p, -2);
+        hipLaunchKernelGGL(bwd_worker_kernel<NW>, dim3(workers), dim3(Geom<NW>::NT),
+                           Geom<NW>::SMEM + kIdxRingBytes, st, p, (int)B_DX);
     } else {
         hipLaunchKernelGGL(bwd_worker_kernel<NW>, dim3(workers), dim3(Geom<NW>::NT),
                            Geom<NW>::SMEM + kIdxRingBytes, st, p, -1);

@@ -344,7 +344,9 @@ __device__ __forceinline__ void combine_task(const FwdParams& p, int block) {
 }
 
 // ------------------------------------------------------------- the worker loop
-// phase < 0: all tasks with scoreboard waits (persistent MegaKernel).
+// phase = -1: all tasks with scoreboard waits (persistent MegaKernel).
+// phase = -2: every GEMM task with scoreboard waits, no tail tasks: the workers leave
+// when the lists are empty and the combine runs as a launch of its own (phase 2).
 // phase >= 0: only that phase's tasks (staged schedule; the waits are already
 // satisfied by stream order).
 template <int NW>
@@ -357,14 +359,14 @@ fwd_worker_kernel(FwdParams p, int phase) {
     const int pass = phase < 0 ? 0 : 1 + phase;
     const int home = xcc_id();
     const bool use_lists = phase != TASK_COMBINE;
-    const bool use_tail = phase < 0 || phase == TASK_COMBINE;
+    const bool use_tail = phase == -1 || phase == TASK_COMBINE;
     // this launch runs GEMM2 tiles: its workers publish their o rows once, when they run out of
     // GEMM work, instead of once per tile
-    const bool publishes = phase < 0 || phase == TASK_GEMM2;
+    const bool publishes = phase == -1 || phase == TASK_GEMM2;
     bool arrived = false;
     unsigned exhausted = 0;
     if (threadIdx.x == 0) {
-        if (phase < 0) worker_started(ctrl, home);
+        if (phase == -1) worker_started(ctrl, home);
         s_task = fetch_task(ctrl, pass, home, exhausted, use_lists, use_tail);
     }
     __syncthreads();
@@ -427,6 +429,10 @@ fwd_worker_kernel(FwdParams p, int phase) {
         __syncthreads();   // every thread has read s_task / s_ok of this round
         if (threadIdx.x == 0) s_task = fetch_finish(pf, ctrl, pass, home, exhausted, use_lists, use_tail);
         __syncthreads();
+    }
+    if (phase == -2) {   // the kernel boundary publishes the rows; only count this worker in
+        if (threadIdx.x == 0) add_relaxed(ctrl + CTRL_DONE, 1);
+        return;
     }
     if (publishes && !arrived) {   // ran out of work without seeing a tail task
         wait_stores();
@@ -503,6 +509,11 @@ static int fwd_launch_nw(FwdParams& p, const moe_opts_t& opts, hipStream_t st) {
         for (int phase = 0; phase < 3; ++phase)
             hipLaunchKernelGGL(fwd_worker_kernel<NW>, dim3(workers), dim3(Geom<NW>::NT),
                                Geom<NW>::SMEM, st, p, phase);
+    } else if (opts.schedule != 1) {   // 0 (default) and 3: GEMM MegaKernel, then the tail tasks
+        hipLaunchKernelGGL(fwd_worker_kernel<NW>, dim3(workers), dim3(Geom<NW>::NT),
+                           Geom<NW>::SMEM, st, p, -2);
+        hipLaunchKernelGGL(fwd_worker_kernel<NW>, dim3(workers), dim3(Geom<NW>::NT),
+                           Geom<NW>::SMEM, st, p, (int)TASK_COMBINE);
     } else {
         hipLaunchKernelGGL(fwd_worker_kernel<NW>, dim3(workers), dim3(Geom<NW>::NT),
                            Geom<NW>::SMEM, st, p, -1);

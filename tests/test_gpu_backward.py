@@ -67,7 +67,7 @@ SMALL = [
 
 
 @pytest.mark.parametrize("kw", SMALL)
-@pytest.mark.parametrize("schedule", [2, 1])
+@pytest.mark.parametrize("schedule", [2, 1, 3])
 @pytest.mark.parametrize("tile_rows", [128, 256])
 def test_backward_matches_oracle(kw, schedule, tile_rows):
     cfg = moe_synth.small_config(**kw)
@@ -97,7 +97,7 @@ def test_backward_is_bitwise_repeatable_and_schedule_independent():
         for key in ref:
             assert torch.equal(ref[key], again[key]), (key, i + 1)
     say("[bwd] determinism across schedules, worker counts and tile heights")
-    for schedule, workers, tile_rows in ((2, 0, 0), (1, 5, 0), (1, 64, 0), (1, 0, 128), (1, 0, 256)):
+    for schedule, workers, tile_rows in ((2, 0, 0), (0, 0, 0), (3, 3, 0), (1, 5, 0), (1, 64, 0), (1, 0, 128), (1, 0, 256)):
         other, _ = gpu_fwd_bwd(cfg, inp, schedule, tile_rows, workers=workers)
         for key in ref:
             assert torch.equal(ref[key], other[key]), (key, schedule, workers, tile_rows)

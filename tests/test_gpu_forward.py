@@ -72,7 +72,7 @@ SMALL = [
 
 
 @pytest.mark.parametrize("kw", SMALL)
-@pytest.mark.parametrize("schedule", [2, 1])
+@pytest.mark.parametrize("schedule", [2, 1, 3])
 @pytest.mark.parametrize("tile_rows", [128, 256])
 def test_forward_matches_oracle(kw, schedule, tile_rows):
     cfg = moe_synth.small_config(**kw)
@@ -118,7 +118,7 @@ def test_forward_is_bitwise_repeatable_and_schedule_independent():
         again, _, _ = gpu_forward(cfg, inp, 1, 0, with_saved=False)
         assert torch.equal(ref, again), f"run {i + 1} differs"
     say("[fwd] determinism across schedules, worker counts and tile heights")
-    for schedule, workers, tile_rows in ((2, 0, 0), (1, 7, 0), (1, 64, 0), (1, 0, 128), (1, 0, 256)):
+    for schedule, workers, tile_rows in ((2, 0, 0), (0, 0, 0), (3, 3, 0), (1, 7, 0), (1, 64, 0), (1, 0, 128), (1, 0, 256)):
         other, _, _ = gpu_forward(cfg, inp, schedule, tile_rows, with_saved=False, workers=workers)
         assert torch.equal(ref, other), (schedule, workers, tile_rows)
 
