@@ -349,7 +349,8 @@ __device__ __forceinline__ void dwgu_task(const BwdParams& p, int e, int mt, int
 }
 
 // ------------------------------------------------------------- phase 4: dX, dtopk_w
-template <int NW>
+// KM = compile-time bound on k (8 or kMaxTopK).
+template <int NW, int KM = kMaxTopK>
 __device__ __forceinline__ void dx_task(const BwdParams& p, int block) {
     const int d = p.s.d, k = p.s.k, T = p.s.T;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -357,12 +358,12 @@ __device__ __forceinline__ void dx_task(const BwdParams& p, int block) {
     for (int tt = wave; tt < kDxTokens; tt += NW) {
         const int t = block * kDxTokens + tt;
         if (t >= T) break;
-        int rows[kMaxTopK];
+        int rows[KM];
 #pragma unroll
-        for (int j = 0; j < kMaxTopK; ++j) rows[j] = (j < k) ? p.inv_perm[(size_t)t * k + j] : -1;
-        float dots[kMaxTopK];
+        for (int j = 0; j < KM; ++j) rows[j] = (j < k) ? p.inv_perm[(size_t)t * k + j] : -1;
+        float dots[KM];
 #pragma unroll
-        for (int j = 0; j < kMaxTopK; ++j) dots[j] = 0.f;
+        for (int j = 0; j < KM; ++j) dots[j] = 0.f;
         for (int c = lane * 8; c < d; c += 64 * 8) {
             // the row loads of eight slots are issued before the first is used
             u32x4_t dyv = zero4();
@@ -371,7 +372,7 @@ __device__ __forceinline__ void dx_task(const BwdParams& p, int block) {
 #pragma unroll
             for (int q = 0; q < 8; ++q) a[q] = 0.f;
 #pragma unroll
-            for (int j0 = 0; j0 < kMaxTopK; j0 += 8) {
+            for (int j0 = 0; j0 < KM; j0 += 8) {
                 if (j0 >= k) break;
                 u32x4_t v[8], ov[8];
 #pragma unroll
@@ -409,7 +410,7 @@ __device__ __forceinline__ void dx_task(const BwdParams& p, int block) {
         }
         if (want_dots) {
 #pragma unroll
-            for (int j = 0; j < kMaxTopK; ++j) {
+            for (int j = 0; j < KM; ++j) {
                 if (j < k) {
                     float s = dots[j];
 #pragma unroll
@@ -526,10 +527,7 @@ bwd_worker_kernel(BwdParams p, int phase) {
         if (threadIdx.x == 0) s_task = fetch_finish(pf, ctrl, pass, home, exhausted, use_lists, use_tail);
         __syncthreads();
     }
-    if (phase == -2) {   // GEMM tasks only: the kernel boundary publishes the rows
-        if (threadIdx.x == 0) add_relaxed(ctrl + CTRL_DONE, 1);
-        return;
-    }
+    if (phase == -2) return;   // GEMM tasks only: the kernel boundary publishes the rows
     if (publishes && !arrived) {
         wait_stores();
         __syncthreads();
@@ -538,6 +536,13 @@ bwd_worker_kernel(BwdParams p, int phase) {
             else add_release(ctrl + CTRL_DONE, 1);
         }
     }
+}
+
+// dX (and dtopk_w) as a plain grid launch behind the GEMM MegaKernel, one workgroup per block
+// of kDxTokens tokens: no scoreboard wait, no task cursor, no LDS.
+template <int NW, int KM>
+__global__ void __launch_bounds__(64 * NW) bwd_tail_kernel(BwdParams p) {
+    dx_task<NW, KM>(p, blockIdx.x);
 }
 
 // ------------------------------------------------------------------ host side
@@ -618,8 +623,13 @@ static int bwd_launch_nw(BwdParams& p, const moe_opts_t& opts, hipStream_t st) {
     } else if (opts.schedule != 1) {   // 0 (default) and 3: GEMM MegaKernel, then the tail tasks
         hipLaunchKernelGGL(bwd_worker_kernel<NW>, dim3(workers), dim3(Geom<NW>::NT),
                            Geom<NW>::SMEM + kIdxRingBytes, st, p, -2);
-        hipLaunchKernelGGL(bwd_worker_kernel<NW>, dim3(workers), dim3(Geom<NW>::NT),
-                           Geom<NW>::SMEM + kIdxRingBytes, st, p, (int)B_DX);
+        const int n_tail = (p.s.T + kDxTokens - 1) / kDxTokens;
+        if (n_tail > 0) {
+            if (p.s.k <= 8)
+                hipLaunchKernelGGL((bwd_tail_kernel<NW, 8>), dim3(n_tail), dim3(Geom<NW>::NT), 0, st, p);
+            else
+                hipLaunchKernelGGL((bwd_tail_kernel<NW, kMaxTopK>), dim3(n_tail), dim3(Geom<NW>::NT), 0, st, p);
+        }
     } else {
         hipLaunchKernelGGL(bwd_worker_kernel<NW>, dim3(workers), dim3(Geom<NW>::NT),
                            Geom<NW>::SMEM + kIdxRingBytes, st, p, -1);

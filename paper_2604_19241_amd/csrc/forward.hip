@@ -286,17 +286,19 @@ __device__ __forceinline__ void gemm2_task(const FwdParams& p, const RowTile rt,
 // ------------------------------------------------------------- combine task
 // y[t] = sum_j w[t,j] * o[row(t,j)], slot order, fp32; one wave per token, 16
 // bytes per lane, no LDS (Section 5.2 "Relay & Reduce Workers").
-template <int NW>
+// KM = compile-time bound on k (8 or kMaxTopK): the row loads of all KM slots are in flight
+// at once, so the smaller bound halves the registers and doubles the waves per SIMD.
+template <int NW, int KM = kMaxTopK>
 __device__ __forceinline__ void combine_task(const FwdParams& p, int block) {
     const int d = p.s.d, k = p.s.k, T = p.s.T;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     for (int tt = wave; tt < kCombineTokens; tt += NW) {
         const int t = block * kCombineTokens + tt;
         if (t >= T) break;
-        int rows[kMaxTopK];
-        float w[kMaxTopK];
+        int rows[KM];
+        float w[KM];
 #pragma unroll
-        for (int j = 0; j < kMaxTopK; ++j) {
+        for (int j = 0; j < KM; ++j) {
             rows[j] = (j < k) ? p.inv_perm[(size_t)t * k + j] : -1;
             w[j] = (j < k) ? p.topk_w[(size_t)t * k + j] : 0.f;
         }
@@ -305,9 +307,9 @@ __device__ __forceinline__ void combine_task(const FwdParams& p, int block) {
         for (int c0 = lane * 8; c0 < d; c0 += 2 * 64 * 8) {
             const int c1 = c0 + 64 * 8;
             const bool two = c1 < d;
-            u32x4_t v0[kMaxTopK], v1[kMaxTopK];
+            u32x4_t v0[KM], v1[KM];
 #pragma unroll
-            for (int j = 0; j < kMaxTopK; ++j) {
+            for (int j = 0; j < KM; ++j) {
                 v0[j] = zero4();
                 v1[j] = zero4();
                 if (j < k && rows[j] >= 0) {
@@ -320,7 +322,7 @@ __device__ __forceinline__ void combine_task(const FwdParams& p, int block) {
 #pragma unroll
             for (int q = 0; q < 8; ++q) a0[q] = a1[q] = 0.f;
 #pragma unroll
-            for (int j = 0; j < kMaxTopK; ++j) {
+            for (int j = 0; j < KM; ++j) {
                 if (j < k && rows[j] >= 0) {   // slot order, local slots only
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
@@ -346,7 +348,7 @@ __device__ __forceinline__ void combine_task(const FwdParams& p, int block) {
 // ------------------------------------------------------------- the worker loop
 // phase = -1: all tasks with scoreboard waits (persistent MegaKernel).
 // phase = -2: every GEMM task with scoreboard waits, no tail tasks: the workers leave
-// when the lists are empty and the combine runs as a launch of its own (phase 2).
+// when the lists are empty and the combine runs as a launch of its own (fwd_tail_kernel).
 // phase >= 0: only that phase's tasks (staged schedule; the waits are already
 // satisfied by stream order).
 template <int NW>
@@ -430,10 +432,7 @@ fwd_worker_kernel(FwdParams p, int phase) {
         if (threadIdx.x == 0) s_task = fetch_finish(pf, ctrl, pass, home, exhausted, use_lists, use_tail);
         __syncthreads();
     }
-    if (phase == -2) {   // the kernel boundary publishes the rows; only count this worker in
-        if (threadIdx.x == 0) add_relaxed(ctrl + CTRL_DONE, 1);
-        return;
-    }
+    if (phase == -2) return;   // the kernel boundary publishes the rows
     if (publishes && !arrived) {   // ran out of work without seeing a tail task
         wait_stores();
         __syncthreads();
@@ -442,6 +441,14 @@ fwd_worker_kernel(FwdParams p, int phase) {
             else add_release(ctrl + CTRL_DONE, 1);
         }
     }
+}
+
+// The combine as a plain grid launch, one workgroup per block of kCombineTokens tokens, for
+// the default schedule: it follows the GEMM MegaKernel in stream order, so it needs no
+// scoreboard wait, no task cursor and no LDS, and as many workgroups as fit share a CU.
+template <int NW, int KM>
+__global__ void __launch_bounds__(64 * NW) fwd_tail_kernel(FwdParams p) {
+    combine_task<NW, KM>(p, blockIdx.x);
 }
 
 // ------------------------------------------------------------------ host side
@@ -512,8 +519,13 @@ static int fwd_launch_nw(FwdParams& p, const moe_opts_t& opts, hipStream_t st) {
     } else if (opts.schedule != 1) {   // 0 (default) and 3: GEMM MegaKernel, then the tail tasks
         hipLaunchKernelGGL(fwd_worker_kernel<NW>, dim3(workers), dim3(Geom<NW>::NT),
                            Geom<NW>::SMEM, st, p, -2);
-        hipLaunchKernelGGL(fwd_worker_kernel<NW>, dim3(workers), dim3(Geom<NW>::NT),
-                           Geom<NW>::SMEM, st, p, (int)TASK_COMBINE);
+        const int n_tail = (p.s.T + kCombineTokens - 1) / kCombineTokens;
+        if (n_tail > 0) {
+            if (p.s.k <= 8)
+                hipLaunchKernelGGL((fwd_tail_kernel<NW, 8>), dim3(n_tail), dim3(Geom<NW>::NT), 0, st, p);
+            else
+                hipLaunchKernelGGL((fwd_tail_kernel<NW, kMaxTopK>), dim3(n_tail), dim3(Geom<NW>::NT), 0, st, p);
+        }
     } else {
         hipLaunchKernelGGL(fwd_worker_kernel<NW>, dim3(workers), dim3(Geom<NW>::NT),
                            Geom<NW>::SMEM, st, p, -1);
