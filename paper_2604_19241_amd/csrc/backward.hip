@@ -445,7 +445,7 @@ bwd_worker_kernel(BwdParams p, int phase) {
     __shared__ int s_task;
     __shared__ int s_ok;
     int* ctrl = p.ctrl;
-    const int pass = phase < 0 ? 0 : 1 + phase;
+    const int pass = phase < 0 ? kPersistentPass : 1 + phase;
     const int home = xcc_id();
     const bool use_lists = phase != B_DX;
     const bool use_tail = phase == -1 || phase == B_DX;

@@ -87,7 +87,12 @@ __device__ __forceinline__ void add_relaxed(int* p, int v) {
 // point to earlier entries of the same list, and an entry is fetched only by a
 // running workgroup, so the lowest unfinished entry of every list can always run.
 constexpr int kQueues = 8;
-constexpr int kPasses = 6;   // cursor sets: 0 = persistent launch, 1+p = staged launch of phase p
+// Cursor sets: 1+p = staged launch of phase p; the last set = persistent launch.  The
+// persistent launches' cursors take one atomic per task from every worker and must not share
+// a 128-byte line with the table (list lengths and bases) that every task fetch reads: with
+// set 0, which does, the whole step was 3 % slower.
+constexpr int kPasses = 7;
+constexpr int kPersistentPass = kPasses - 1;
 
 // Control words at the head of a forward/backward workspace.
 enum CtrlWord {
