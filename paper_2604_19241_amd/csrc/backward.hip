@@ -171,8 +171,9 @@ __global__ void __launch_bounds__(1024) bwd_prologue_kernel(BwdParams p) {
 }
 
 // ------------------------------------------------------------- phase 0: dH
-template <int NW>
-__device__ __forceinline__ void dh_task(const BwdParams& p, const RowTile rt, int ct, char* smem) {
+template <int NW, class Hook>
+__device__ __forceinline__ void dh_task(const BwdParams& p, const RowTile rt, int ct, char* smem,
+                                        Hook after_mainloop) {
     typedef Geom<NW> G;
     const int d = p.s.d, I = p.s.I;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -195,6 +196,7 @@ __device__ __forceinline__ void dh_task(const BwdParams& p, const RowTile rt, in
     }
     f32x16_t acc[8];
     mma_mainloop_direct<NW>(al, bl, d / BK, smem, wave * 32 < rt.rows, acc);
+    after_mainloop();
     // epilogue: SwiGLU backward with the saved G, U of the same rows and columns
     const int col = n0 + (lane & 31) * 8;
     if (col < I) {
@@ -230,8 +232,9 @@ __device__ __forceinline__ void dh_task(const BwdParams& p, const RowTile rt, in
 }
 
 // ------------------------------------------------------------- phase 2: dXp
-template <int NW>
-__device__ __forceinline__ void dxp_task(const BwdParams& p, const RowTile rt, int ct, char* smem) {
+template <int NW, class Hook>
+__device__ __forceinline__ void dxp_task(const BwdParams& p, const RowTile rt, int ct, char* smem,
+                                        Hook after_mainloop) {
     typedef Geom<NW> G;
     const int d = p.s.d, I = p.s.I;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -255,6 +258,7 @@ __device__ __forceinline__ void dxp_task(const BwdParams& p, const RowTile rt, i
     bl.switch_stage = I / BK;
     f32x16_t acc[8];
     mma_mainloop_direct<NW>(al, bl, 2 * I / BK, smem, wave * 32 < rt.rows, acc);
+    after_mainloop();
     const int col = n0 + (lane & 31) * 8;
     if (col < d) {
 #pragma unroll
@@ -269,9 +273,9 @@ __device__ __forceinline__ void dxp_task(const BwdParams& p, const RowTile rt, i
 // ------------------------------------------------------------- phase 1: dW_down
 // dW_down[e][i][c] = sum over the expert's rows r (ascending) of h[r][i] * dO[r][c].
 // Output tile: 32*NW rows of I by 256 columns of d.
-template <int NW>
+template <int NW, class Hook>
 __device__ __forceinline__ void dwd_task(const BwdParams& p, int e, int mt, int nt, int r0, int cnt,
-                                         char* smem) {
+                                         char* smem, Hook after_mainloop) {
     typedef Geom<NW> G;
     const int d = p.s.d, I = p.s.I;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -293,6 +297,7 @@ __device__ __forceinline__ void dwd_task(const BwdParams& p, int e, int mt, int 
     bl.src = p.dy + (size_t)min(nt * BN + BL::TG::chunk() * 8, d - 8) * 2;
     f32x16_t acc[8];
     mma_mainloop<NW>(al, bl, (cnt + BK - 1) / BK, smem, true, acc);
+    after_mainloop();
     const int col = nt * BN + (lane & 31) * 8;
     if (col < d) {
 #pragma unroll
@@ -308,9 +313,9 @@ __device__ __forceinline__ void dwd_task(const BwdParams& p, int e, int mt, int 
 // dW_gate[e][c][i] = sum_r x[tok(r)][c] * dG[r][i]; dW_up likewise with dU.
 // Output tile: 32*NW rows of d by 128 columns of I, for both matrices at once.
 // B-tile chunk nb: even -> 8 columns of dG, odd -> the same 8 columns of dU.
-template <int NW>
+template <int NW, class Hook>
 __device__ __forceinline__ void dwgu_task(const BwdParams& p, int e, int mt, int nt, int r0, int cnt,
-                                          char* smem) {
+                                          char* smem, Hook after_mainloop) {
     typedef Geom<NW> G;
     const int d = p.s.d, I = p.s.I;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -335,6 +340,7 @@ __device__ __forceinline__ void dwgu_task(const BwdParams& p, int e, int mt, int
     }
     f32x16_t acc[8];
     mma_mainloop<NW>(al, bl, (cnt + BK - 1) / BK, smem, true, acc);
+    after_mainloop();
     const int nb = lane & 31;
     const int icol = nt * 128 + (nb >> 1) * 8;
     char* dst = (nb & 1) ? p.dw_up : p.dw_gate;
@@ -467,10 +473,15 @@ bwd_worker_kernel(BwdParams p, int phase) {
 #ifdef UNIEP_PROFILE_BWD
         const long long t_ev = wall_clock64();
 #endif
+        // issued behind the main loop of the task (see the forward worker)
         PendingFetch pf;
         pf.q = -1;
         pf.id = 0;
-        if (threadIdx.x == 0) pf = fetch_issue(ctrl, pass, home, exhausted, use_lists);
+        bool issued = false;
+        auto issue = [&]() {
+            if (!issued && threadIdx.x == 0) pf = fetch_issue(ctrl, pass, home, exhausted, use_lists);
+            issued = true;
+        };
         if (id >= 0) {
             const Task task = p.tasks[id];
             const int type = task_type(task), ct = task_ct(task);
@@ -478,7 +489,7 @@ bwd_worker_kernel(BwdParams p, int phase) {
                 // staged launch: another phase's task
             } else if (type == B_DH) {
                 const RowTile rt = task_row_tile(task);
-                dh_task<NW>(p, rt, ct, smem);
+                dh_task<NW>(p, rt, ct, smem, issue);
                 wait_stores();
                 __syncthreads();   // the write-through dG|dU stores of every wave have completed
                 if (threadIdx.x == 0) {
@@ -487,14 +498,14 @@ bwd_worker_kernel(BwdParams p, int phase) {
                 }
                 TRACE_B(B_DH + 16 * rt.rows);
             } else if (type == B_DWD) {
-                dwd_task<NW>(p, task_expert(task), task.idx, ct, task.row0, task.rows, smem);
+                dwd_task<NW>(p, task_expert(task), task.idx, ct, task.row0, task.rows, smem, issue);
                 TRACE_B(B_DWD);
             } else if (type == B_DXP) {
                 if (threadIdx.x == 0) s_ok = wait_ge(p.flag_rt + task.idx, p.nct_dh, ctrl, p.spin_ticks);
                 __syncthreads();
                 if (s_ok) {
                     const RowTile rt = task_row_tile(task);
-                    dxp_task<NW>(p, rt, ct, smem);
+                    dxp_task<NW>(p, rt, ct, smem, issue);
                     TRACE_B(B_DXP + 16 * rt.rows);
                 }
             } else {
@@ -503,7 +514,7 @@ bwd_worker_kernel(BwdParams p, int phase) {
                 const int need = (task.rows + Geom<NW>::BM - 1) / Geom<NW>::BM * p.nct_dh;
                 if (threadIdx.x == 0) s_ok = wait_ge(p.flag_e + e, need, ctrl, p.spin_ticks);
                 __syncthreads();
-                if (s_ok) dwgu_task<NW>(p, e, task.idx, ct, task.row0, task.rows, smem);
+                if (s_ok) dwgu_task<NW>(p, e, task.idx, ct, task.row0, task.rows, smem, issue);
                 TRACE_B(B_DWGU);
             }
         } else {
@@ -523,6 +534,7 @@ bwd_worker_kernel(BwdParams p, int phase) {
             if (s_ok) dx_task<NW>(p, -1 - id);
             TRACE_B(B_DX);
         }
+        issue();           // tasks without a main loop (tail, skipped, given up)
         __syncthreads();
         if (threadIdx.x == 0) s_task = fetch_finish(pf, ctrl, pass, home, exhausted, use_lists, use_tail);
         __syncthreads();

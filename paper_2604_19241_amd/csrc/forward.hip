@@ -160,9 +160,9 @@ __global__ void __launch_bounds__(1024) fwd_prologue_kernel(FwdParams p) {
 // h[row0.., ct*128 .. +128) = silu(x_e W_gate) * (x_e W_up) for one row tile.
 // B-tile chunk nb: even -> 8 gate columns, odd -> the same 8 up columns, so the
 // lanes 2q and 2q+1 hold G and U of the same columns.
-template <int NW>
+template <int NW, class Hook>
 __device__ __forceinline__ void gemm1_task(const FwdParams& p, const RowTile rt, int ct,
-                                           char* smem) {
+                                           char* smem, Hook after_mainloop) {
     const long long t_start = PROF_NOW();
     typedef Geom<NW> G;
     const int d = p.s.d, I = p.s.I, k = p.s.k;
@@ -205,6 +205,7 @@ __device__ __forceinline__ void gemm1_task(const FwdParams& p, const RowTile rt,
 #else
     mma_mainloop<NW>(al, bl, d / BK, smem, wave * 32 < rt.rows, acc);
 #endif
+    after_mainloop();
     PROF_ADD(TASK_GEMM1, 2, PROF_NOW() - t_start);
     PROF_ADD(TASK_GEMM1, 5, d / BK);
     const long long t_main = PROF_NOW();
@@ -247,9 +248,9 @@ __device__ __forceinline__ void gemm1_task(const FwdParams& p, const RowTile rt,
 
 // ------------------------------------------------------------- GEMM2 task
 // o[row0.., ct*256 .. +256) = h_e W_down[e] for one row tile.
-template <int NW>
+template <int NW, class Hook>
 __device__ __forceinline__ void gemm2_task(const FwdParams& p, const RowTile rt, int ct,
-                                           char* smem) {
+                                           char* smem, Hook after_mainloop) {
     const long long t_start = PROF_NOW();
     typedef Geom<NW> G;
     const int d = p.s.d, I = p.s.I;
@@ -270,6 +271,7 @@ __device__ __forceinline__ void gemm2_task(const FwdParams& p, const RowTile rt,
     }
     f32x16_t acc[8];
     mma_mainloop_direct<NW>(al, bl, I / BK, smem, wave * 32 < rt.rows, acc);
+    after_mainloop();
     PROF_ADD(TASK_GEMM2, 2, PROF_NOW() - t_start);
     PROF_ADD(TASK_GEMM2, 5, I / BK);
     const int col = n0 + (lane & 31) * 8;
@@ -379,10 +381,17 @@ fwd_worker_kernel(FwdParams p, int phase) {
         if (id == kFetchDone) break;
         const long long t_ev = PROF_NOW();
         (void)t_ev;
+        // The cursor atomic of the next task is issued behind the main loop of this one: vector
+        // memory results return in order, so an atomic issued ahead of a tile would hold back
+        // the first loads of its wave by the atomic's round trip.
         PendingFetch pf;
         pf.q = -1;
         pf.id = 0;
-        if (threadIdx.x == 0) pf = fetch_issue(ctrl, pass, home, exhausted, use_lists);
+        bool issued = false;
+        auto issue = [&]() {
+            if (!issued && threadIdx.x == 0) pf = fetch_issue(ctrl, pass, home, exhausted, use_lists);
+            issued = true;
+        };
         if (id >= 0) {
             const Task task = p.tasks[id];
             const int type = task_type(task), ct = task_ct(task);
@@ -394,7 +403,7 @@ fwd_worker_kernel(FwdParams p, int phase) {
                 if (rt.rows == Geom<NW>::BM) PROF_ADD(TASK_GEMM1, 4, PROF_NOW() - t_ev);
                 const long long t_g1 = PROF_NOW();
 #endif
-                gemm1_task<NW>(p, rt, ct, smem);
+                gemm1_task<NW>(p, rt, ct, smem, issue);
                 wait_stores();
                 __syncthreads();   // the write-through h stores of every wave have completed
                 if (threadIdx.x == 0) add_relaxed(p.flag1 + task.idx, 1);
@@ -407,7 +416,7 @@ fwd_worker_kernel(FwdParams p, int phase) {
                 __syncthreads();
                 if (s_ok) {
                     const RowTile rt = task_row_tile(task);
-                    gemm2_task<NW>(p, rt, ct, smem);
+                    gemm2_task<NW>(p, rt, ct, smem, issue);
                     TRACE_EVENT(n_ev, TASK_GEMM2 + 16 * rt.rows, t_ev);
                 }
             }
@@ -428,6 +437,7 @@ fwd_worker_kernel(FwdParams p, int phase) {
             if (s_ok) combine_task<NW>(p, -1 - id);
             TRACE_EVENT(n_ev, TASK_COMBINE, t_ev);
         }
+        issue();           // tasks without a main loop (tail, skipped, given up)
         __syncthreads();   // every thread has read s_task / s_ok of this round
         if (threadIdx.x == 0) s_task = fetch_finish(pf, ctrl, pass, home, exhausted, use_lists, use_tail);
         __syncthreads();
