@@ -7,9 +7,10 @@ workload has a backward).  Prints ONE JSON line:
 
   value       useful TFLOP/s of the whole step (6*A*d*I forward + 12*A*d*I
               backward, A = realised routed rows) -- the metric the benchmark spec names
-  roofline    the dominant kernel (the backward MegaKernel when the workload has a
-              backward, else the forward MegaKernel) against the bf16 dense MFMA peak;
-              roofline_forward carries the forward MegaKernel beside it
+  roofline    the dominant kernel (the backward GEMM MegaKernel when the workload has a
+              backward, else the forward one) against the bf16 dense MFMA peak, timed by HIP
+              events around the call without its tail kernel; roofline_forward carries the
+              forward GEMM MegaKernel beside it
   cpu_baseline  the CPU oracle timed on a bounded sample of the same workload
 
 Usage: python bench.py [--gpus 1] [--steps K] [--warmup W] [--config N]
@@ -286,11 +287,32 @@ def main():
     fwd_tflops = f_fwd / (ms_fwd[0] * 1e-3) / 1e12
     # waves per workgroup (tile height 32 * nw): 8 unless 128-row tiles are asked for
     nw = 4 if args.tile_rows == 128 else 8
+    # The GEMM MegaKernels alone: the same calls without their tail kernel (combine / dX).  With
+    # the other schedules the tail runs inside the worker launches and the whole call is timed.
+    split = args.schedule in (0, 3)
+    opts_mega = moe.make_opts(schedule=args.schedule, tile_rows=args.tile_rows, workers=args.workers,
+                              skip_tail=1 if split else 0)
 
-    def roof(kernel, what, flops, ms):
+    def fwd_mega():
+        moe.moe_fused_forward(shape, dev["x"], dev["w_gate"], dev["w_up"], dev["w_down"],
+                              state["r"], y=y, saved=saved, ws=ws_fwd, opts=opts_mega)
+
+    def bwd_mega():
+        moe.moe_fused_backward(shape, dev["dy"], dev["x"], dev["w_gate"], dev["w_up"],
+                               dev["w_down"], state["r"], saved, ws=ws_bwd, opts=opts_mega,
+                               out=grads.get("out"))
+
+    ms_fwd_mega = event_ms(fwd_mega, n)
+    ms_bwd_mega = event_ms(bwd_mega, n) if has_bwd else None
+    fwd()                       # leave complete outputs behind
+    if has_bwd:
+        bwd()
+
+    def roof(kernel, what, flops, ms, ms_call):
         tf = flops / (ms[0] * 1e-3) / 1e12
         return {
-            "kernel": f"{kernel} ({what}; the HIP events also span its small prologue launches)",
+            "kernel": f"{kernel} ({what}; the HIP events also span its prologue launches, "
+                      f"15-22 us, and with schedule 1 or 2 the tail tasks)",
             "bound": "mfma",
             "achieved": tf,
             "peak": MFMA_BF16_PEAK_TFLOPS,
@@ -299,11 +321,13 @@ def main():
             "traffic": measured_traffic(cfg.name, kernel),
             "flops_per_launch": flops,
             "avg_ms": ms[0], "median_ms": ms[1], "min_ms": ms[2],
+            "tail_kernel_ms": (ms_call[0] - ms[0]) if split else None,
         }
 
-    roof_fwd = roof(f"fwd_worker_kernel<{nw}>", "forward MegaKernel, 6*A*d*I flop per launch", f_fwd, ms_fwd)
-    roof_bwd = roof(f"bwd_worker_kernel<{nw}>", "backward MegaKernel, 12*A*d*I flop per launch",
-                    f_bwd, ms_bwd) if has_bwd else None
+    roof_fwd = roof(f"fwd_worker_kernel<{nw}>", "forward GEMM MegaKernel, 6*A*d*I flop per launch",
+                    f_fwd, ms_fwd_mega, ms_fwd)
+    roof_bwd = roof(f"bwd_worker_kernel<{nw}>", "backward GEMM MegaKernel, 12*A*d*I flop per launch",
+                    f_bwd, ms_bwd_mega, ms_bwd) if has_bwd else None
     roofline = roof_bwd if has_bwd else roof_fwd
     counts = state["r"].counts.cpu().tolist()
     out = {

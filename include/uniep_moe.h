@@ -87,7 +87,11 @@ typedef struct {
     int32_t spin_limit_ms; /* bound on every scoreboard wait; 0 = 2000 ms.  A wait that
                               exceeds it sets MOE_ERR_DEVICE in the workspace and drains */
     int32_t tile_rows;     /* rows per GEMM row tile: 0 = default (256), or 128 / 256 */
-    int32_t reserved[4];   /* must be 0 */
+    int32_t skip_tail;     /* measurement aid, 0 or 1: with the default schedule, 1 leaves out the
+                              tail kernel (combine / dX), so that y / dx and dtopk_w are not
+                              written and a timer around the call sees the GEMM MegaKernel and
+                              its prologue alone */
+    int32_t reserved[3];   /* must be 0 */
 } moe_opts_t;
 
 /* Bytes each call needs (host outputs; any may be NULL).  `saved_bytes` is the

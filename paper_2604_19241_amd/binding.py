@@ -36,7 +36,7 @@ class MoERoutingC(ctypes.Structure):
 class MoEOpts(ctypes.Structure):
     _fields_ = [("schedule", ctypes.c_int32), ("workers", ctypes.c_int32),
                 ("spin_limit_ms", ctypes.c_int32), ("tile_rows", ctypes.c_int32),
-                ("reserved", ctypes.c_int32 * 4)]
+                ("skip_tail", ctypes.c_int32), ("reserved", ctypes.c_int32 * 3)]
 
 
 class MoEError(RuntimeError):
@@ -79,9 +79,10 @@ def make_shape(T, d, E, k, I, e_start=0, e_count=None) -> MoEShape:
                     int(E if e_count is None else e_count))
 
 
-def make_opts(schedule=0, workers=0, spin_limit_ms=0, tile_rows=0) -> MoEOpts:
+def make_opts(schedule=0, workers=0, spin_limit_ms=0, tile_rows=0, skip_tail=0) -> MoEOpts:
     o = MoEOpts()
     o.schedule, o.workers, o.spin_limit_ms, o.tile_rows = schedule, workers, spin_limit_ms, tile_rows
+    o.skip_tail = skip_tail
     return o
 
 

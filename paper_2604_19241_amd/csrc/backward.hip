@@ -636,7 +636,7 @@ static int bwd_launch_nw(BwdParams& p, const moe_opts_t& opts, hipStream_t st) {
         hipLaunchKernelGGL(bwd_worker_kernel<NW>, dim3(workers), dim3(Geom<NW>::NT),
                            Geom<NW>::SMEM + kIdxRingBytes, st, p, -2);
         const int n_tail = (p.s.T + kDxTokens - 1) / kDxTokens;
-        if (n_tail > 0) {
+        if (n_tail > 0 && !opts.skip_tail) {
             if (p.s.k <= 8)
                 hipLaunchKernelGGL((bwd_tail_kernel<NW, 8>), dim3(n_tail), dim3(Geom<NW>::NT), 0, st, p);
             else

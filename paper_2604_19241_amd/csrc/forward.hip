@@ -530,7 +530,7 @@ static int fwd_launch_nw(FwdParams& p, const moe_opts_t& opts, hipStream_t st) {
         hipLaunchKernelGGL(fwd_worker_kernel<NW>, dim3(workers), dim3(Geom<NW>::NT),
                            Geom<NW>::SMEM, st, p, -2);
         const int n_tail = (p.s.T + kCombineTokens - 1) / kCombineTokens;
-        if (n_tail > 0) {
+        if (n_tail > 0 && !opts.skip_tail) {
             if (p.s.k <= 8)
                 hipLaunchKernelGGL((fwd_tail_kernel<NW, 8>), dim3(n_tail), dim3(Geom<NW>::NT), 0, st, p);
             else

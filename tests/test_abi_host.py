@@ -103,6 +103,11 @@ def test_null_and_misaligned_pointers_are_rejected_before_any_launch(lib):
     assert fwd(opts=ctypes.byref(bad)) == b.MOE_ERR_ARG
     bad = b.make_opts(tile_rows=64)
     assert fwd(opts=ctypes.byref(bad)) == b.MOE_ERR_ARG
+    bad = b.make_opts(skip_tail=2)
+    assert fwd(opts=ctypes.byref(bad)) == b.MOE_ERR_ARG
+    bad = b.make_opts()
+    bad.reserved[0] = 1
+    assert fwd(opts=ctypes.byref(bad)) == b.MOE_ERR_ARG
     # backward needs the stash
     rc = lib.moe_fused_backward(ctypes.byref(s), fake, fake, fake, fake, fake, ctypes.byref(r_ok),
                                 None, fake, fake, fake, fake, None, fake, big, None, None)
