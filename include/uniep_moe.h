@@ -143,7 +143,11 @@ int moe_fused_forward(const moe_shape_t* shape, const void* x, const void* w_gat
  * bitwise reproducible).  Experts with no rows get exact zeros.
  *   saved    the stash a forward call with the same inputs filled (required)
  *   dx       [T,d] bf16;  dw_gate, dw_up [e_count,d,I] bf16;  dw_down [e_count,I,d] bf16
- *   dtopk_w  [T,k] fp32 = <dy[t], o[row(t,j)]> (0 for non-local slots), or NULL
+ *   dtopk_w  [T,k] fp32 = <dy[t], o[row(t,j)]> (0 for non-local slots), or NULL.
+ *            Evaluated as sum_i (dy[t] W_down[e]^T)[i] * h[r][i] from the fp32
+ *            accumulators of the dH tiles and the stashed h, column tiles added
+ *            in ascending order: the same number without the bf16 rounding of
+ *            o, and the stashed o is not read.
  *   ws       bwd_ws bytes */
 int moe_fused_backward(const moe_shape_t* shape, const void* dy, const void* x,
                        const void* w_gate, const void* w_up, const void* w_down,

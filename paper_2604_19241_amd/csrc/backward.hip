@@ -51,6 +51,7 @@ struct BwdParams {
     float* row_w;
     char* dgu;   // [A,2I]
     char* dxp;   // [A,d]
+    float* dots; // [nct_dh][T*k] per dH column tile: sum over its columns of (dY W_down^T)[r][i] * h[r][i]
     int nct_dh, nct_dxp;        // column tiles of phase 0 (256 of I) and phase 2 (256 of d)
     int mt_dwd, nt_dwd;         // dW_down tiles per expert: ceil(I/256) x ceil(d/256)
     int mt_dwgu, nt_dwgu;       // dW_gate/up tiles per expert: ceil(d/256) x ceil(I/128)
@@ -178,11 +179,14 @@ __device__ __forceinline__ void dh_task(const BwdParams& p, const RowTile rt, in
     const int d = p.s.d, I = p.s.I;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int kc = tid & 7;
-    DirectRowLoader<true> al;   // dO = gate * dY, gathered and scaled on the fly
+    // A = dY gathered; the gate multiplies the fp32 accumulators in the epilogue, which also
+    // needs the unscaled product: <dY[t], o[r]> = sum_i (dY[t] W_down^T)[i] * h[r][i].
+    DirectRowLoader<false> al;
+    float gate;   // of tile row wave*32 + lane%32
     {
         const int row = rt.row0 + min(wave * 32 + (lane & 31), rt.rows - 1);
         al.rp = p.dy + ((size_t)p.row_tok[row] * d + (lane >> 5) * 32) * 2;
-        al.sc = p.row_w[row];
+        gate = p.row_w[row];
     }
     typedef RowLoader<G::NT, BN, false> BL;   // B rows are rows of W_down[e]: k (= d) contiguous
     BL bl;
@@ -199,34 +203,47 @@ __device__ __forceinline__ void dh_task(const BwdParams& p, const RowTile rt, in
     after_mainloop();
     // epilogue: SwiGLU backward with the saved G, U of the same rows and columns
     const int col = n0 + (lane & 31) * 8;
-    if (col < I) {
+    const bool want_dots = p.dtopk_w != nullptr;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int m = wave * 32 + frag_row(v, lane);
-            if (m < rt.rows) {
-                const size_t base = ((size_t)(rt.row0 + m) * 2 * I + col) * 2;
-                const u32x4_t gv = *(const u32x4_t*)(p.gu + base);
-                const u32x4_t uv = *(const u32x4_t*)(p.gu + base + (size_t)I * 2);
-                float dg[8], du[8];
+    for (int v = 0; v < 16; ++v) {
+        const int m = wave * 32 + frag_row(v, lane);
+        const float gt = __shfl(gate, frag_row(v, lane));
+        float dot = 0.f;
+        if (col < I && m < rt.rows) {
+            const size_t base = ((size_t)(rt.row0 + m) * 2 * I + col) * 2;
+            const u32x4_t gv = *(const u32x4_t*)(p.gu + base);
+            const u32x4_t uv = *(const u32x4_t*)(p.gu + base + (size_t)I * 2);
+            u32x4_t hv = zero4();   // the h that GEMM2 multiplied (bf16), not silu(g) * u of the rounded g, u
+            if (want_dots) hv = *(const u32x4_t*)(p.h + ((size_t)(rt.row0 + m) * I + col) * 2);
+            float dg[8], du[8];
 #pragma unroll
-                for (int f = 0; f < 8; ++f) {
-                    const float g = (f & 1) ? bf16_hi(gv[f >> 1]) : bf16_lo(gv[f >> 1]);
-                    const float u = (f & 1) ? bf16_hi(uv[f >> 1]) : bf16_lo(uv[f >> 1]);
-                    const float dh = acc[f][v];
-                    const float sg = sigmoid_f(g);
-                    du[f] = dh * (g * sg);
-                    dg[f] = dh * u * (sg * (1.f + g * (1.f - sg)));
-                }
-                u32x4_t dgp, dup;
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    dgp[q] = pack_bf16x2(dg[2 * q], dg[2 * q + 1]);
-                    dup[q] = pack_bf16x2(du[2 * q], du[2 * q + 1]);
-                }
-                // consumed by dXp / dW_gate / dW_up tiles on any XCD
-                store_wt16(p.dgu + base, dgp);
-                store_wt16(p.dgu + base + (size_t)I * 2, dup);
+            for (int f = 0; f < 8; ++f) {
+                const float g = (f & 1) ? bf16_hi(gv[f >> 1]) : bf16_lo(gv[f >> 1]);
+                const float u = (f & 1) ? bf16_hi(uv[f >> 1]) : bf16_lo(uv[f >> 1]);
+                const float raw = acc[f][v];
+                const float dh = gt * raw;
+                const float sg = sigmoid_f(g);
+                const float silu = g * sg;
+                dot += raw * ((f & 1) ? bf16_hi(hv[f >> 1]) : bf16_lo(hv[f >> 1]));
+                du[f] = dh * silu;
+                dg[f] = dh * u * (sg * (1.f + g * (1.f - sg)));
             }
+            u32x4_t dgp, dup;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                dgp[q] = pack_bf16x2(dg[2 * q], dg[2 * q + 1]);
+                dup[q] = pack_bf16x2(du[2 * q], du[2 * q + 1]);
+            }
+            // consumed by dXp / dW_gate / dW_up tiles on any XCD
+            store_wt16(p.dgu + base, dgp);
+            store_wt16(p.dgu + base + (size_t)I * 2, dup);
+        }
+        if (want_dots) {
+            // the 32 lanes of a half hold the 256 columns of row m: fixed butterfly order
+#pragma unroll
+            for (int off = 16; off >= 1; off >>= 1) dot += __shfl_xor(dot, off);
+            if ((lane & 31) == 0 && m < rt.rows)
+                p.dots[(size_t)ct * ((size_t)p.s.T * p.s.k) + rt.row0 + m] = dot;
         }
     }
 }
@@ -367,29 +384,21 @@ __device__ __forceinline__ void dx_task(const BwdParams& p, int block) {
         int rows[KM];
 #pragma unroll
         for (int j = 0; j < KM; ++j) rows[j] = (j < k) ? p.inv_perm[(size_t)t * k + j] : -1;
-        float dots[KM];
-#pragma unroll
-        for (int j = 0; j < KM; ++j) dots[j] = 0.f;
         for (int c = lane * 8; c < d; c += 64 * 8) {
             // the row loads of eight slots are issued before the first is used
-            u32x4_t dyv = zero4();
-            if (want_dots) dyv = *(const u32x4_t*)(p.dy + ((size_t)t * d + c) * 2);
             float a[8];
 #pragma unroll
             for (int q = 0; q < 8; ++q) a[q] = 0.f;
 #pragma unroll
             for (int j0 = 0; j0 < KM; j0 += 8) {
                 if (j0 >= k) break;
-                u32x4_t v[8], ov[8];
+                u32x4_t v[8];
 #pragma unroll
                 for (int jj = 0; jj < 8; ++jj) {
                     const int j = j0 + jj;
                     v[jj] = zero4();
-                    ov[jj] = zero4();
-                    if (j < k && rows[j] >= 0) {
+                    if (j < k && rows[j] >= 0)
                         v[jj] = *(const u32x4_t*)(p.dxp + ((size_t)rows[j] * d + c) * 2);
-                        if (want_dots) ov[jj] = *(const u32x4_t*)(p.o + ((size_t)rows[j] * d + c) * 2);
-                    }
                 }
 #pragma unroll
                 for (int jj = 0; jj < 8; ++jj) {
@@ -400,12 +409,6 @@ __device__ __forceinline__ void dx_task(const BwdParams& p, int block) {
                             a[2 * q] += bf16_lo(v[jj][q]);
                             a[2 * q + 1] += bf16_hi(v[jj][q]);
                         }
-                        if (want_dots) {
-#pragma unroll
-                            for (int q = 0; q < 4; ++q)
-                                dots[j] += bf16_lo(dyv[q]) * bf16_lo(ov[jj][q]) +
-                                           bf16_hi(dyv[q]) * bf16_hi(ov[jj][q]);
-                        }
                     }
                 }
             }
@@ -414,16 +417,14 @@ __device__ __forceinline__ void dx_task(const BwdParams& p, int block) {
             for (int q = 0; q < 4; ++q) out[q] = pack_bf16x2(a[2 * q], a[2 * q + 1]);
             store_stream16(p.dx + ((size_t)t * d + c) * 2, out);
         }
-        if (want_dots) {
-#pragma unroll
-            for (int j = 0; j < KM; ++j) {
-                if (j < k) {
-                    float s = dots[j];
-#pragma unroll
-                    for (int off = 32; off >= 1; off >>= 1) s += __shfl_xor(s, off);
-                    if (lane == 0) p.dtopk_w[(size_t)t * k + j] = (rows[j] >= 0) ? s : 0.f;
-                }
-            }
+        if (want_dots && lane < k) {
+            // dtopk_w[t][j] = <dY[t], o[row]>: the partial sums of the row's dH column tiles,
+            // added in column-tile order; 0 for a slot whose expert is not local
+            const int r = p.inv_perm[(size_t)t * k + lane];
+            float s = 0.f;
+            if (r >= 0)
+                for (int ct = 0; ct < p.nct_dh; ++ct) s += p.dots[(size_t)ct * ((size_t)T * k) + r];
+            p.dtopk_w[(size_t)t * k + lane] = s;
         }
     }
 }
@@ -560,7 +561,7 @@ __global__ void __launch_bounds__(64 * NW) bwd_tail_kernel(BwdParams p) {
 // ------------------------------------------------------------------ host side
 
 struct BwdLayout {
-    size_t ctrl, flag_rt, flag_e, tasks, row_tok, row_w, dgu, dxp, total;
+    size_t ctrl, flag_rt, flag_e, tasks, row_tok, row_w, dgu, dxp, dots, total;
     int max_rt, nct_dh, nct_dxp, mt_dwd, nt_dwd, mt_dwgu, nt_dwgu;
 };
 
@@ -586,6 +587,7 @@ static BwdLayout bwd_layout(const moe_shape_t& s, int bm) {
     L.row_w = off;   off = align_up(off + A_cap * sizeof(float), 256);
     L.dgu = off;     off = align_up(off + A_cap * 2 * s.I * 2, 256);
     L.dxp = off;     off = align_up(off + A_cap * s.d * 2, 256);
+    L.dots = off;    off = align_up(off + (size_t)L.nct_dh * A_cap * sizeof(float), 256);
     L.total = off;
     return L;
 }
@@ -681,6 +683,7 @@ int bwd_launch(const moe_shape_t& s, const void* dy, const void* x, const void* 
     p.row_w = (float*)(ws + L.row_w);
     p.dgu = ws + L.dgu;
     p.dxp = ws + L.dxp;
+    p.dots = (float*)(ws + L.dots);
     p.nct_dh = L.nct_dh;
     p.nct_dxp = L.nct_dxp;
     p.mt_dwd = L.mt_dwd;
