@@ -384,38 +384,45 @@ __device__ __forceinline__ void dx_task(const BwdParams& p, int block) {
         int rows[KM];
 #pragma unroll
         for (int j = 0; j < KM; ++j) rows[j] = (j < k) ? p.inv_perm[(size_t)t * k + j] : -1;
-        for (int c = lane * 8; c < d; c += 64 * 8) {
-            // the row loads of eight slots are issued before the first is used
-            float a[8];
+        // two 16-byte column pieces per lane and round, as in the forward combine: all 2k row
+        // loads are issued before the first is used
+        for (int c0 = lane * 8; c0 < d; c0 += 2 * 64 * 8) {
+            const int c1 = c0 + 64 * 8;
+            const bool two = c1 < d;
+            u32x4_t v0[KM], v1[KM];
 #pragma unroll
-            for (int q = 0; q < 8; ++q) a[q] = 0.f;
-#pragma unroll
-            for (int j0 = 0; j0 < KM; j0 += 8) {
-                if (j0 >= k) break;
-                u32x4_t v[8];
-#pragma unroll
-                for (int jj = 0; jj < 8; ++jj) {
-                    const int j = j0 + jj;
-                    v[jj] = zero4();
-                    if (j < k && rows[j] >= 0)
-                        v[jj] = *(const u32x4_t*)(p.dxp + ((size_t)rows[j] * d + c) * 2);
+            for (int j = 0; j < KM; ++j) {
+                v0[j] = zero4();
+                v1[j] = zero4();
+                if (j < k && rows[j] >= 0) {
+                    const char* src = p.dxp + (size_t)rows[j] * d * 2;
+                    v0[j] = *(const u32x4_t*)(src + (size_t)c0 * 2);
+                    if (two) v1[j] = *(const u32x4_t*)(src + (size_t)c1 * 2);
                 }
+            }
+            float a0[8], a1[8];
 #pragma unroll
-                for (int jj = 0; jj < 8; ++jj) {
-                    const int j = j0 + jj;
-                    if (j < k && rows[j] >= 0) {   // slot order, local slots only
+            for (int q = 0; q < 8; ++q) a0[q] = a1[q] = 0.f;
 #pragma unroll
-                        for (int q = 0; q < 4; ++q) {
-                            a[2 * q] += bf16_lo(v[jj][q]);
-                            a[2 * q + 1] += bf16_hi(v[jj][q]);
-                        }
+            for (int j = 0; j < KM; ++j) {
+                if (j < k && rows[j] >= 0) {   // slot order, local slots only
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        a0[2 * q] += bf16_lo(v0[j][q]);
+                        a0[2 * q + 1] += bf16_hi(v0[j][q]);
+                        a1[2 * q] += bf16_lo(v1[j][q]);
+                        a1[2 * q + 1] += bf16_hi(v1[j][q]);
                     }
                 }
             }
-            u32x4_t out;
+            u32x4_t o0, o1;
 #pragma unroll
-            for (int q = 0; q < 4; ++q) out[q] = pack_bf16x2(a[2 * q], a[2 * q + 1]);
-            store_stream16(p.dx + ((size_t)t * d + c) * 2, out);
+            for (int q = 0; q < 4; ++q) {
+                o0[q] = pack_bf16x2(a0[2 * q], a0[2 * q + 1]);
+                o1[q] = pack_bf16x2(a1[2 * q], a1[2 * q + 1]);
+            }
+            store_stream16(p.dx + ((size_t)t * d + c0) * 2, o0);
+            if (two) store_stream16(p.dx + ((size_t)t * d + c1) * 2, o1);
         }
         if (want_dots && lane < k) {
             // dtopk_w[t][j] = <dY[t], o[row]>: the partial sums of the row's dH column tiles,
