@@ -210,6 +210,61 @@ int moe_global_map(const moe_shape_t* shape, int32_t W, int32_t rank, const moe_
  * hot path never calls it). */
 int moe_device_status(const void* ws, void* stream);
 
+/* ---- Analytical performance model and configuration search (host only) -------
+ * Section 4.2, Algorithm 2 and its equations; search space of Section 6.2.  The
+ * model predicts the latency of one expert-parallel MoE pass (dispatch + up GEMM,
+ * SwiGLU, down GEMM + combine) for a split of the chip's workers between
+ * communication, relay, reduce and GEMM work, and the search returns the split
+ * with the smallest predicted latency.  Nothing here touches a GPU: all pointers
+ * are host pointers, the calls are synchronous and allocate only host memory.
+ *
+ * Hardware H: n_sm workers (SMs / CUs), p_peak FLOP/s, beta_hbm and beta_link
+ * (one direction) in bytes/s, w_sat = warps (waves) that saturate a bandwidth,
+ * tau_sync seconds per tile for its scoreboard traffic, mu[i] = GEMM utilisation
+ * with 8, 16, 32 warps per worker (the paper: 0.7, 0.65, 0.6; w_sat 1024; 2 us).
+ * Problem P: n_tok tokens per rank, h_dim, h_inter, n_exp experts over `world`
+ * ranks (n_exp % world == 0), top_k, GEMM block b_m x b_n, elem_bytes per element.
+ * What the paper leaves open is read as follows: balanced routing; X = W (1 -
+ * (1 - 1/W)^k) destination ranks per token; V_nvl = n_tok X S_tok for dispatch
+ * and combine; the relay copies V_hbm = n_tok (k - X) S_tok; the reduce reads
+ * V_hbm_total = n_tok k S_tok; S_tok = h_dim elem_bytes; per rank n_tok k rows
+ * over n_exp / world experts, ceil(rows / b_m) row tiles each, ceil(2 h_inter /
+ * b_n) column tiles in the up GEMM and ceil(h_dim / b_n) in the down GEMM.
+ * Configuration C: n_disp, n_relay, n_comb, n_red workers and `warps` in
+ * {8, 16, 32}; valid iff 1 <= n_disp < n_sm, 1 <= n_comb < n_sm, n_relay >= 1,
+ * 1 <= n_red <= n_sm and n_disp + n_relay < n_sm (Section 4.1). */
+typedef struct {
+    int32_t n_sm, w_sat;
+    double p_peak, beta_hbm, beta_link, tau_sync;
+    double mu[3];
+} moe_perf_hw_t;
+typedef struct {
+    int32_t n_tok, h_dim, h_inter, n_exp, top_k, world, b_m, b_n, elem_bytes;
+} moe_perf_problem_t;
+typedef struct {
+    int32_t n_disp, n_relay, n_comb, n_red, warps;
+} moe_perf_config_t;
+typedef struct {   /* every intermediate of Algorithm 2's loop body, seconds */
+    double t_up, t_down, l_swiglu, l_disp, l_up, l_s1, l_comb, t_red, l_down, l_s2, l_total;
+} moe_perf_latency_t;
+
+/* Algorithm 2's loop body for one configuration.  MOE_ERR_ARG for a NULL pointer,
+ * MOE_ERR_SHAPE for values outside the ranges above or an invalid configuration. */
+int moe_perf_model_eval(const moe_perf_hw_t* hw, const moe_perf_problem_t* problem,
+                        const moe_perf_config_t* config, moe_perf_latency_t* out);
+
+/* Algorithm 2 over the space of Section 6.2: n_disp, n_comb in {4, 8, ..,
+ * 4 floor(n_sm / 4)}; n_relay in {1, 5, 9, ..} up to n_disp / 2; n_red in {1, 17,
+ * 33, ..} up to n_sm with n_sm itself appended when the steps miss it; warps in
+ * {8, 16, 32}.  Invalid configurations are counted in *n_enumerated and skipped.
+ * Ties keep the configuration met first in the nested order n_disp, n_relay,
+ * n_comb, n_red, warps.  *best_latency receives the winner's intermediates;
+ * n_enumerated and n_valid may be NULL.  MOE_ERR_SHAPE if no configuration is
+ * valid (n_sm < 6) or hw / problem are out of range. */
+int moe_perf_model_search(const moe_perf_hw_t* hw, const moe_perf_problem_t* problem,
+                          moe_perf_config_t* best, moe_perf_latency_t* best_latency,
+                          int64_t* n_enumerated, int64_t* n_valid);
+
 /* Static string for a return code. */
 const char* moe_status_string(int code);
 

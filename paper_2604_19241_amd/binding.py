@@ -21,7 +21,8 @@ MOE_ERR_ARG, MOE_ERR_SHAPE, MOE_ERR_WORKSPACE, MOE_ERR_HIP, MOE_ERR_DEVICE = -1,
 
 EXPORTS = ("moe_workspace_bytes", "moe_saved_layout", "moe_route", "moe_fused_forward",
            "moe_fused_backward", "moe_route_backward", "moe_global_map", "moe_device_status",
-           "moe_status_string", "moe_calibration_copy")
+           "moe_status_string", "moe_calibration_copy", "moe_perf_model_eval",
+           "moe_perf_model_search")
 
 
 class MoEShape(ctypes.Structure):
@@ -282,3 +283,58 @@ def saved_views(shape: MoEShape, saved: torch.Tensor) -> dict:
         return saved[off:off + A * cols * 2].view(torch.bfloat16).view(A, cols)
 
     return {"gu": view(L["gu"], 2 * shape.I), "h": view(L["h"], shape.I), "o": view(L["o"], shape.d)}
+
+
+# ---- analytical performance model and configuration search (host only) -------
+
+class MoEPerfHw(ctypes.Structure):
+    _fields_ = [("n_sm", ctypes.c_int32), ("w_sat", ctypes.c_int32), ("p_peak", ctypes.c_double),
+                ("beta_hbm", ctypes.c_double), ("beta_link", ctypes.c_double),
+                ("tau_sync", ctypes.c_double), ("mu", ctypes.c_double * 3)]
+
+
+class MoEPerfProblem(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("n_tok", "h_dim", "h_inter", "n_exp", "top_k", "world",
+                                              "b_m", "b_n", "elem_bytes")]
+
+
+class MoEPerfConfig(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("n_disp", "n_relay", "n_comb", "n_red", "warps")]
+
+
+PERF_LATENCY_FIELDS = ("t_up", "t_down", "l_swiglu", "l_disp", "l_up", "l_s1", "l_comb", "t_red",
+                       "l_down", "l_s2", "l_total")
+
+
+class MoEPerfLatency(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_double) for n in PERF_LATENCY_FIELDS]
+
+
+def make_perf_hw(n_sm, p_peak, beta_hbm, beta_link, w_sat=1024, tau_sync=2e-6,
+                 mu=(0.7, 0.65, 0.6)) -> MoEPerfHw:
+    return MoEPerfHw(int(n_sm), int(w_sat), float(p_peak), float(beta_hbm), float(beta_link),
+                     float(tau_sync), (ctypes.c_double * 3)(*map(float, mu)))
+
+
+def make_perf_problem(n_tok, h_dim, h_inter, n_exp, top_k, world, b_m=128, b_n=128,
+                      elem_bytes=2) -> MoEPerfProblem:
+    return MoEPerfProblem(*map(int, (n_tok, h_dim, h_inter, n_exp, top_k, world, b_m, b_n, elem_bytes)))
+
+
+def moe_perf_model_eval(hw: MoEPerfHw, problem: MoEPerfProblem, config) -> dict:
+    c = config if isinstance(config, MoEPerfConfig) else MoEPerfConfig(*map(int, config))
+    out = MoEPerfLatency()
+    _check(load_library().moe_perf_model_eval(ctypes.byref(hw), ctypes.byref(problem), ctypes.byref(c),
+                                              ctypes.byref(out)), "moe_perf_model_eval")
+    return {n: getattr(out, n) for n in PERF_LATENCY_FIELDS}
+
+
+def moe_perf_model_search(hw: MoEPerfHw, problem: MoEPerfProblem) -> dict:
+    best, lat = MoEPerfConfig(), MoEPerfLatency()
+    n_enum, n_valid = ctypes.c_int64(0), ctypes.c_int64(0)
+    _check(load_library().moe_perf_model_search(ctypes.byref(hw), ctypes.byref(problem), ctypes.byref(best),
+                                                ctypes.byref(lat), ctypes.byref(n_enum),
+                                                ctypes.byref(n_valid)), "moe_perf_model_search")
+    return {"config": (best.n_disp, best.n_relay, best.n_comb, best.n_red, best.warps),
+            "latency": {n: getattr(lat, n) for n in PERF_LATENCY_FIELDS},
+            "n_enumerated": int(n_enum.value), "n_valid": int(n_valid.value)}

@@ -15,7 +15,7 @@ PKG = Path(__file__).resolve().parent
 CSRC = PKG / "csrc"
 LIB = PKG / "libuniep_moe.so"
 BUILD = PKG.parent / "_build"
-SOURCES = ["route.hip", "forward.hip", "backward.hip", "api.hip"]
+SOURCES = ["route.hip", "forward.hip", "backward.hip", "api.hip", "perf_model.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
