@@ -91,7 +91,14 @@ typedef struct {
                               tail kernel (combine / dX), so that y / dx and dtopk_w are not
                               written and a timer around the call sees the GEMM MegaKernel and
                               its prologue alone */
-    int32_t reserved[3];   /* must be 0 */
+    int32_t dw_accumulate; /* moe_fused_backward only, 0 or 1.  1: dw_gate, dw_up, dw_down are fp32
+                              buffers of the same shapes (16-byte aligned) and the weight
+                              gradients are ADDED to them in fp32, straight from the
+                              accumulators (no bf16 rounding): the gradient-accumulation buffer
+                              of a mixed-precision training loop.  Experts without rows are left
+                              untouched.  Every element is updated by exactly one tile, so the
+                              result is as reproducible as with 0. */
+    int32_t reserved[2];   /* must be 0 */
 } moe_opts_t;
 
 /* Bytes each call needs (host outputs; any may be NULL).  `saved_bytes` is the
@@ -143,6 +150,7 @@ int moe_fused_forward(const moe_shape_t* shape, const void* x, const void* w_gat
  * bitwise reproducible).  Experts with no rows get exact zeros.
  *   saved    the stash a forward call with the same inputs filled (required)
  *   dx       [T,d] bf16;  dw_gate, dw_up [e_count,d,I] bf16;  dw_down [e_count,I,d] bf16
+ *            (overwritten; with opts->dw_accumulate = 1: fp32, added to)
  *   dtopk_w  [T,k] fp32 = <dy[t], o[row(t,j)]> (0 for non-local slots), or NULL.
  *            Evaluated as sum_i (dy[t] W_down[e]^T)[i] * h[r][i] from the fp32
  *            accumulators of the dH tiles and the stashed h, column tiles added

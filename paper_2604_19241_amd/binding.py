@@ -37,7 +37,8 @@ class MoERoutingC(ctypes.Structure):
 class MoEOpts(ctypes.Structure):
     _fields_ = [("schedule", ctypes.c_int32), ("workers", ctypes.c_int32),
                 ("spin_limit_ms", ctypes.c_int32), ("tile_rows", ctypes.c_int32),
-                ("skip_tail", ctypes.c_int32), ("reserved", ctypes.c_int32 * 3)]
+                ("skip_tail", ctypes.c_int32), ("dw_accumulate", ctypes.c_int32),
+                ("reserved", ctypes.c_int32 * 2)]
 
 
 class MoEError(RuntimeError):
@@ -80,10 +81,12 @@ def make_shape(T, d, E, k, I, e_start=0, e_count=None) -> MoEShape:
                     int(E if e_count is None else e_count))
 
 
-def make_opts(schedule=0, workers=0, spin_limit_ms=0, tile_rows=0, skip_tail=0) -> MoEOpts:
+def make_opts(schedule=0, workers=0, spin_limit_ms=0, tile_rows=0, skip_tail=0,
+              dw_accumulate=0) -> MoEOpts:
     o = MoEOpts()
     o.schedule, o.workers, o.spin_limit_ms, o.tile_rows = schedule, workers, spin_limit_ms, tile_rows
     o.skip_tail = skip_tail
+    o.dw_accumulate = dw_accumulate
     return o
 
 
@@ -175,6 +178,12 @@ def moe_fused_backward(shape: MoEShape, dy, x, w_gate, w_up, w_down, routing: Ro
     for t in (dy, x, w_gate, w_up, w_down):
         assert t.is_cuda and t.dtype == torch.bfloat16 and t.is_contiguous()
     assert tuple(dy.shape) == (shape.T, shape.d)
+    if opts is not None and opts.dw_accumulate:
+        # the caller's fp32 gradient buffers are added to
+        assert out is not None, "dw_accumulate needs the caller's fp32 dw_gate / dw_up / dw_down in `out`"
+        for key, w in (("dw_gate", w_gate), ("dw_up", w_up), ("dw_down", w_down)):
+            g = out[key]
+            assert g.is_cuda and g.dtype == torch.float32 and g.is_contiguous() and g.shape == w.shape
     if out is None:
         out = {
             "dx": torch.empty_like(x),

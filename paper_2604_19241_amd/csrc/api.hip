@@ -56,7 +56,8 @@ int check_opts(const moe_opts_t* o, moe_opts_t* out) {
     if (d.schedule < 0 || d.schedule > 3 || d.workers < 0 || d.spin_limit_ms < 0) return MOE_ERR_ARG;
     if (d.tile_rows != 0 && d.tile_rows != 128 && d.tile_rows != 256) return MOE_ERR_ARG;
     if (d.skip_tail != 0 && d.skip_tail != 1) return MOE_ERR_ARG;
-    for (int i = 0; i < 3; ++i)
+    if (d.dw_accumulate != 0 && d.dw_accumulate != 1) return MOE_ERR_ARG;
+    for (int i = 0; i < 2; ++i)
         if (d.reserved[i] != 0) return MOE_ERR_ARG;
     *out = d;
     return MOE_OK;

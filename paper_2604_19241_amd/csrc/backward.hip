@@ -287,10 +287,23 @@ __device__ __forceinline__ void dxp_task(const BwdParams& p, const RowTile rt, i
     }
 }
 
+// Weight gradients added to an fp32 gradient buffer (a training loop's main gradient) instead
+// of written as bf16: q[0..8) += the lane's 8 consecutive columns of accumulator element v.
+// Every element belongs to exactly one tile, so the read-modify-write needs no atomic and the
+// sum does not depend on the schedule.
+__device__ __forceinline__ void accumulate_row8(float* q, const f32x16_t (&acc)[8], int v) {
+    typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+    f32x4_t a = ((const f32x4_t*)q)[0], b = ((const f32x4_t*)q)[1];
+    a += f32x4_t{acc[0][v], acc[1][v], acc[2][v], acc[3][v]};
+    b += f32x4_t{acc[4][v], acc[5][v], acc[6][v], acc[7][v]};
+    __builtin_nontemporal_store(a, (f32x4_t*)q);
+    __builtin_nontemporal_store(b, (f32x4_t*)q + 1);
+}
+
 // ------------------------------------------------------------- phase 1: dW_down
 // dW_down[e][i][c] = sum over the expert's rows r (ascending) of h[r][i] * dO[r][c].
 // Output tile: 32*NW rows of I by 256 columns of d.
-template <int NW, class Hook>
+template <int NW, bool ACC, class Hook>
 __device__ __forceinline__ void dwd_task(const BwdParams& p, int e, int mt, int nt, int r0, int cnt,
                                          char* smem, Hook after_mainloop) {
     typedef Geom<NW> G;
@@ -320,8 +333,13 @@ __device__ __forceinline__ void dwd_task(const BwdParams& p, int e, int mt, int 
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int m = mt * G::BM + tr_tile_row<NW>(wave * 32 + frag_row(v, lane));
-            if (m < I)
-                store_stream16(p.dw_down + (((size_t)e * I + m) * d + col) * 2, pack_row8(acc, v));
+            if (m < I) {
+                if (ACC) {
+                    if (cnt > 0) accumulate_row8((float*)p.dw_down + ((size_t)e * I + m) * d + col, acc, v);
+                } else {
+                    store_stream16(p.dw_down + (((size_t)e * I + m) * d + col) * 2, pack_row8(acc, v));
+                }
+            }
         }
     }
 }
@@ -330,7 +348,7 @@ __device__ __forceinline__ void dwd_task(const BwdParams& p, int e, int mt, int 
 // dW_gate[e][c][i] = sum_r x[tok(r)][c] * dG[r][i]; dW_up likewise with dU.
 // Output tile: 32*NW rows of d by 128 columns of I, for both matrices at once.
 // B-tile chunk nb: even -> 8 columns of dG, odd -> the same 8 columns of dU.
-template <int NW, class Hook>
+template <int NW, bool ACC, class Hook>
 __device__ __forceinline__ void dwgu_task(const BwdParams& p, int e, int mt, int nt, int r0, int cnt,
                                           char* smem, Hook after_mainloop) {
     typedef Geom<NW> G;
@@ -365,8 +383,13 @@ __device__ __forceinline__ void dwgu_task(const BwdParams& p, int e, int mt, int
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int m = mt * G::BM + tr_tile_row<NW>(wave * 32 + frag_row(v, lane));
-            if (m < d)
-                store_stream16(dst + (((size_t)e * d + m) * I + icol) * 2, pack_row8(acc, v));
+            if (m < d) {
+                if (ACC) {
+                    if (cnt > 0) accumulate_row8((float*)dst + ((size_t)e * d + m) * I + icol, acc, v);
+                } else {
+                    store_stream16(dst + (((size_t)e * d + m) * I + icol) * 2, pack_row8(acc, v));
+                }
+            }
         }
     }
 }
@@ -452,10 +475,9 @@ extern "C" int moe_debug_trace_bwd(long long* out) {
 #endif
 
 // ------------------------------------------------------------- worker loop
-template <int NW>
-__global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
-bwd_worker_kernel(BwdParams p, int phase) {
-    extern __shared__ __attribute__((aligned(16))) char smem[];
+// ACC: the weight gradients are added to fp32 buffers (moe_opts_t.dw_accumulate).
+template <int NW, bool ACC>
+__device__ __forceinline__ void bwd_worker_body(const BwdParams& p, int phase, char* smem) {
     __shared__ int s_task;
     __shared__ int s_ok;
     int* ctrl = p.ctrl;
@@ -506,7 +528,7 @@ bwd_worker_kernel(BwdParams p, int phase) {
                 }
                 TRACE_B(B_DH + 16 * rt.rows);
             } else if (type == B_DWD) {
-                dwd_task<NW>(p, task_expert(task), task.idx, ct, task.row0, task.rows, smem, issue);
+                dwd_task<NW, ACC>(p, task_expert(task), task.idx, ct, task.row0, task.rows, smem, issue);
                 TRACE_B(B_DWD);
             } else if (type == B_DXP) {
                 if (threadIdx.x == 0) s_ok = wait_ge(p.flag_rt + task.idx, p.nct_dh, ctrl, p.spin_ticks);
@@ -522,7 +544,7 @@ bwd_worker_kernel(BwdParams p, int phase) {
                 const int need = (task.rows + Geom<NW>::BM - 1) / Geom<NW>::BM * p.nct_dh;
                 if (threadIdx.x == 0) s_ok = wait_ge(p.flag_e + e, need, ctrl, p.spin_ticks);
                 __syncthreads();
-                if (s_ok) dwgu_task<NW>(p, e, task.idx, ct, task.row0, task.rows, smem, issue);
+                if (s_ok) dwgu_task<NW, ACC>(p, e, task.idx, ct, task.row0, task.rows, smem, issue);
                 TRACE_B(B_DWGU);
             }
         } else {
@@ -556,6 +578,19 @@ bwd_worker_kernel(BwdParams p, int phase) {
             else add_release(ctrl + CTRL_DONE, 1);
         }
     }
+}
+
+template <int NW>
+__global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
+bwd_worker_kernel(BwdParams p, int phase) {
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    bwd_worker_body<NW, false>(p, phase, smem);
+}
+template <int NW>
+__global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
+bwd_worker_acc_kernel(BwdParams p, int phase) {
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    bwd_worker_body<NW, true>(p, phase, smem);
 }
 
 // dX (and dtopk_w) as a plain grid launch behind the GEMM MegaKernel, one workgroup per block
@@ -601,22 +636,25 @@ static BwdLayout bwd_layout(const moe_shape_t& s, int bm) {
 
 size_t bwd_workspace_bytes(const moe_shape_t& s) { return bwd_layout(s, 128).total; }   // 128-row tiles need the most tasks
 
-static int g_bwd_workers[16];
+static int g_bwd_workers[32];
 
-template <int NW>
+template <int NW, bool ACC>
 static int bwd_resident_workers(int* out) {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess) return MOE_ERR_HIP;
-    const int slot = (dev & 7) * 2 + (NW == 8 ? 1 : 0);
+    const int slot = ((dev & 7) * 2 + (NW == 8 ? 1 : 0)) * 2 + (ACC ? 1 : 0);
     if (g_bwd_workers[slot] == 0) {
-        if (hipFuncSetAttribute((const void*)bwd_worker_kernel<NW>,
-                                hipFuncAttributeMaxDynamicSharedMemorySize,
+        const void* fn = ACC ? (const void*)bwd_worker_acc_kernel<NW> : (const void*)bwd_worker_kernel<NW>;
+        if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize,
                                 Geom<NW>::SMEM + kIdxRingBytes) != hipSuccess)
             return MOE_ERR_HIP;
         int per_cu = 0, cus = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, bwd_worker_kernel<NW>, Geom<NW>::NT,
-                                                         Geom<NW>::SMEM + kIdxRingBytes) != hipSuccess)
-            return MOE_ERR_HIP;
+        const hipError_t occ = ACC
+            ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, bwd_worker_acc_kernel<NW>, Geom<NW>::NT,
+                                                           Geom<NW>::SMEM + kIdxRingBytes)
+            : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, bwd_worker_kernel<NW>, Geom<NW>::NT,
+                                                           Geom<NW>::SMEM + kIdxRingBytes);
+        if (occ != hipSuccess) return MOE_ERR_HIP;
         if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
             return MOE_ERR_HIP;
         if (per_cu < 1 || cus < 1) return MOE_ERR_HIP;
@@ -626,10 +664,20 @@ static int bwd_resident_workers(int* out) {
     return MOE_OK;
 }
 
-template <int NW>
+template <int NW, bool ACC>
+static void launch_worker(const BwdParams& p, int workers, int phase, hipStream_t st) {
+    if (ACC)
+        hipLaunchKernelGGL(bwd_worker_acc_kernel<NW>, dim3(workers), dim3(Geom<NW>::NT),
+                           Geom<NW>::SMEM + kIdxRingBytes, st, p, phase);
+    else
+        hipLaunchKernelGGL(bwd_worker_kernel<NW>, dim3(workers), dim3(Geom<NW>::NT),
+                           Geom<NW>::SMEM + kIdxRingBytes, st, p, phase);
+}
+
+template <int NW, bool ACC>
 static int bwd_launch_nw(BwdParams& p, const moe_opts_t& opts, hipStream_t st) {
     int resident = 0;
-    int rc = bwd_resident_workers<NW>(&resident);
+    int rc = bwd_resident_workers<NW, ACC>(&resident);
     if (rc != MOE_OK) return rc;
     const int workers = opts.workers > 0 ? min(opts.workers, resident) : resident;
     p.workers = workers;
@@ -638,12 +686,9 @@ static int bwd_launch_nw(BwdParams& p, const moe_opts_t& opts, hipStream_t st) {
         hipLaunchKernelGGL(row_meta_kernel, dim3((A_cap + 255) / 256), dim3(256), 0, st, p);
     hipLaunchKernelGGL(bwd_prologue_kernel<Geom<NW>::BM>, dim3(1), dim3(1024), 0, st, p);
     if (opts.schedule == 2) {
-        for (int phase = 0; phase < 5; ++phase)
-            hipLaunchKernelGGL(bwd_worker_kernel<NW>, dim3(workers), dim3(Geom<NW>::NT),
-                               Geom<NW>::SMEM + kIdxRingBytes, st, p, phase);
+        for (int phase = 0; phase < 5; ++phase) launch_worker<NW, ACC>(p, workers, phase, st);
     } else if (opts.schedule != 1) {   // 0 (default) and 3: GEMM MegaKernel, then the tail tasks
-        hipLaunchKernelGGL(bwd_worker_kernel<NW>, dim3(workers), dim3(Geom<NW>::NT),
-                           Geom<NW>::SMEM + kIdxRingBytes, st, p, -2);
+        launch_worker<NW, ACC>(p, workers, -2, st);
         const int n_tail = (p.s.T + kDxTokens - 1) / kDxTokens;
         if (n_tail > 0 && !opts.skip_tail) {
             if (p.s.k <= 8)
@@ -652,8 +697,7 @@ static int bwd_launch_nw(BwdParams& p, const moe_opts_t& opts, hipStream_t st) {
                 hipLaunchKernelGGL((bwd_tail_kernel<NW, kMaxTopK>), dim3(n_tail), dim3(Geom<NW>::NT), 0, st, p);
         }
     } else {
-        hipLaunchKernelGGL(bwd_worker_kernel<NW>, dim3(workers), dim3(Geom<NW>::NT),
-                           Geom<NW>::SMEM + kIdxRingBytes, st, p, -1);
+        launch_worker<NW, ACC>(p, workers, -1, st);
     }
     return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
@@ -699,7 +743,9 @@ int bwd_launch(const moe_shape_t& s, const void* dy, const void* x, const void* 
     p.nt_dwgu = L.nt_dwgu;
     const int ms = opts.spin_limit_ms > 0 ? opts.spin_limit_ms : 2000;
     p.spin_ticks = (long long)ms * 100000ll;
-    return nw == 4 ? bwd_launch_nw<4>(p, opts, st) : bwd_launch_nw<8>(p, opts, st);
+    if (opts.dw_accumulate)
+        return nw == 4 ? bwd_launch_nw<4, true>(p, opts, st) : bwd_launch_nw<8, true>(p, opts, st);
+    return nw == 4 ? bwd_launch_nw<4, false>(p, opts, st) : bwd_launch_nw<8, false>(p, opts, st);
 }
 
 }  // namespace uniep

@@ -105,9 +105,13 @@ def test_null_and_misaligned_pointers_are_rejected_before_any_launch(lib):
     assert fwd(opts=ctypes.byref(bad)) == b.MOE_ERR_ARG
     bad = b.make_opts(skip_tail=2)
     assert fwd(opts=ctypes.byref(bad)) == b.MOE_ERR_ARG
-    bad = b.make_opts()
-    bad.reserved[0] = 1
+    bad = b.make_opts(dw_accumulate=2)
     assert fwd(opts=ctypes.byref(bad)) == b.MOE_ERR_ARG
+    for i in range(2):
+        bad = b.make_opts()
+        bad.reserved[i] = 1
+        assert fwd(opts=ctypes.byref(bad)) == b.MOE_ERR_ARG
+    assert ctypes.sizeof(b.MoEOpts) == 32
     # backward needs the stash
     rc = lib.moe_fused_backward(ctypes.byref(s), fake, fake, fake, fake, fake, ctypes.byref(r_ok),
                                 None, fake, fake, fake, fake, None, fake, big, None, None)

@@ -148,3 +148,54 @@ def test_forward_backward_empty_batch():
     assert y.shape == (0, cfg.d) and g["dx"].shape == (0, cfg.d)
     for key in ("dw_gate", "dw_up", "dw_down"):
         assert (g[key] == 0).all(), key
+
+
+@pytest.mark.parametrize("schedule,tile_rows", [(0, 0), (1, 0), (2, 0), (0, 128)])
+def test_backward_accumulates_weight_gradients_in_fp32(schedule, tile_rows):
+    """opts.dw_accumulate: the fp32 accumulators are added to the caller's fp32 buffers.  Onto
+    zeros the result rounds to exactly the bf16 gradients of the plain call; a second call
+    doubles it exactly; onto a non-zero buffer it is the fp32 sum, element for element; experts
+    without rows are not touched (a -0.0 stays -0.0); dX and dtopk_w do not change."""
+    import paper_2604_19241_amd as moe
+    cfg = moe_synth.small_config(T=1100, d=320, E=12, k=3, I=448, e_start=2, e_count=9)
+    inp = scaled_inputs(cfg, 31, 4.0)
+    inp["logits"][:, 5] = -30.0   # a local expert that no token selects
+    say(f"[bwd accumulate] {cfg.shape_dict()} schedule={schedule} tile_rows={tile_rows}")
+    plain, routing = gpu_fwd_bwd(cfg, inp, schedule, tile_rows)
+    counts = routing.counts.cpu().numpy()
+    assert (counts == 0).any() and (counts > 256).any()
+    shape = moe.make_shape(**cfg.shape_dict())
+    dev = {key: v.cuda() for key, v in inp.items()}
+    saved = moe.alloc_saved(shape, "cuda")
+    moe.moe_fused_forward(shape, dev["x"], dev["w_gate"], dev["w_up"], dev["w_down"], routing, saved=saved)
+    opts = moe.make_opts(schedule=schedule, tile_rows=tile_rows, spin_limit_ms=500, dw_accumulate=1)
+    wkeys = ("dw_gate", "dw_up", "dw_down")
+
+    def run(main):
+        out = {"dx": torch.empty_like(dev["x"]), "dtopk_w": torch.empty((shape.T, shape.k), dtype=torch.float32, device="cuda")}
+        out.update(main)
+        return moe.moe_fused_backward(shape, dev["dy"], dev["x"], dev["w_gate"], dev["w_up"], dev["w_down"],
+                                      routing, saved, opts=opts, out=out)
+
+    zeros = {key: torch.zeros_like(dev["w_" + key[3:]], dtype=torch.float32) for key in wkeys}
+    once = run(zeros)
+    first = {key: once[key].clone() for key in wkeys}
+    for key in wkeys:
+        assert torch.equal(first[key].to(torch.bfloat16), plain[key]), key
+    assert torch.equal(once["dx"], plain["dx"]) and torch.equal(once["dtopk_w"], plain["dtopk_w"])
+    twice = run(once)     # the same buffers again
+    for key in wkeys:
+        assert torch.equal(twice[key], 2.0 * first[key]), key
+    gen = torch.Generator(device="cuda").manual_seed(77)
+    main = {key: torch.randn(first[key].shape, generator=gen, device="cuda", dtype=torch.float32) for key in wkeys}
+    idle = [int(e) for e in np.nonzero(counts == 0)[0]]
+    for key in wkeys:
+        for e in idle:
+            main[key][e].fill_(-0.0)
+    want = {key: main[key] + first[key] for key in wkeys}
+    got = run({key: main[key].clone() for key in wkeys})
+    for key in wkeys:
+        busy = [e for e in range(cfg.e_count) if e not in idle]
+        assert torch.equal(got[key][busy], want[key][busy]), key
+        for e in idle:
+            assert torch.equal(got[key][e].view(torch.int32), main[key][e].view(torch.int32)), (key, e)
