@@ -147,18 +147,23 @@ __global__ void __launch_bounds__(1024) bwd_prologue_kernel(BwdParams p) {
         Task* ta = p.tasks + s_ta[x];
         Task* tb = p.tasks + s_tb[x];
         const int r0 = s_r0[x], rows_x = s_plan.cost[x];
-        for (int i = lane; i < n_dh; i += 64) {
-            const int j = i / p.nct_dh;
-            ta[i] = Task{rt0 + j, task_code(B_DH, x, i % p.nct_dh), r0 + j * BM, min(BM, rows_x - j * BM)};
-        }
-        for (int i = lane; i < per_dwd; i += 64)
-            ta[n_dh + i] = Task{i / p.nt_dwd, task_code(B_DWD, x, i % p.nt_dwd), r0, rows_x};
-        for (int i = lane; i < n_dxp; i += 64) {
-            const int j = i / p.nct_dxp;
-            tb[i] = Task{rt0 + j, task_code(B_DXP, x, i % p.nct_dxp), r0 + j * BM, min(BM, rows_x - j * BM)};
-        }
-        for (int i = lane; i < per_dwgu; i += 64)
-            tb[n_dxp + i] = Task{i / p.nt_dwgu, task_code(B_DWGU, x, i % p.nt_dwgu), r0, rows_x};
+        // every block in the grouped order of block_pos(): row-tile GEMMs over (row tile, column
+        // tile), weight-gradient GEMMs over (output row tile, output column tile)
+        const int nt_x = (rows_x + BM - 1) / BM;
+        for_each_tile(lane, nt_x, p.nct_dh, [&](int j, int ct) {
+            ta[block_pos<false>(j, ct, nt_x, p.nct_dh)] =
+                Task{rt0 + j, task_code(B_DH, x, ct), r0 + j * BM, min(BM, rows_x - j * BM)};
+        });
+        for_each_tile(lane, p.mt_dwd, p.nt_dwd, [&](int mt, int nt) {
+            ta[n_dh + block_pos<false>(mt, nt, p.mt_dwd, p.nt_dwd)] = Task{mt, task_code(B_DWD, x, nt), r0, rows_x};
+        });
+        for_each_tile(lane, nt_x, p.nct_dxp, [&](int j, int ct) {
+            tb[block_pos<false>(j, ct, nt_x, p.nct_dxp)] =
+                Task{rt0 + j, task_code(B_DXP, x, ct), r0 + j * BM, min(BM, rows_x - j * BM)};
+        });
+        for_each_tile(lane, p.mt_dwgu, p.nt_dwgu, [&](int mt, int nt) {
+            tb[n_dxp + block_pos<false>(mt, nt, p.mt_dwgu, p.nt_dwgu)] = Task{mt, task_code(B_DWGU, x, nt), r0, rows_x};
+        });
     }
     if (e < CTRL_WORDS) {
         int v = 0;

@@ -72,6 +72,7 @@ __global__ void __launch_bounds__(1024) fwd_prologue_kernel(FwdParams p) {
     __shared__ int32_t s_scan[kMaxExperts];
     __shared__ int32_t s_g1[kMaxExperts];
     __shared__ int32_t s_g2[kMaxExperts];
+    __shared__ int32_t s_nt[kMaxExperts];
     __shared__ int32_t s_qbase[kQueues + 1];
     __shared__ int32_t s_qlen[kQueues];
     __shared__ int32_t s_lag;
@@ -85,6 +86,7 @@ __global__ void __launch_bounds__(1024) fwd_prologue_kernel(FwdParams p) {
     }
     s_plan.cost[e] = cnt;
     s_scan[e] = nt;
+    s_nt[e] = nt;
     s_g1[e] = nt * p.nct1;
     s_g2[e] = nt * p.nct2;
     __syncthreads();
@@ -134,16 +136,16 @@ __global__ void __launch_bounds__(1024) fwd_prologue_kernel(FwdParams p) {
         const int rt0 = s_rt0[x], lane = e & 63;
         Task* t1 = p.tasks + s_t1[x];
         Task* t2 = p.tasks + s_t2[x];
-        const int n1 = s_g1[x], n2 = s_g2[x];
         const int r0 = s_r0[x], rows_x = s_plan.cost[x];
-        for (int i = lane; i < n1; i += 64) {
-            const int j = i / p.nct1;
-            t1[i] = Task{rt0 + j, task_code(TASK_GEMM1, x, i % p.nct1), r0 + j * BM, min(BM, rows_x - j * BM)};
-        }
-        for (int i = lane; i < n2; i += 64) {
-            const int j = i / p.nct2;
-            t2[i] = Task{rt0 + j, task_code(TASK_GEMM2, x, i % p.nct2), r0 + j * BM, min(BM, rows_x - j * BM)};
-        }
+        const int nt_x = s_nt[x];
+        for_each_tile(lane, nt_x, p.nct1, [&](int j, int ct) {
+            t1[block_pos<true>(j, ct, nt_x, p.nct1)] =
+                Task{rt0 + j, task_code(TASK_GEMM1, x, ct), r0 + j * BM, min(BM, rows_x - j * BM)};
+        });
+        for_each_tile(lane, nt_x, p.nct2, [&](int j, int ct) {
+            t2[block_pos<true>(j, ct, nt_x, p.nct2)] =
+                Task{rt0 + j, task_code(TASK_GEMM2, x, ct), r0 + j * BM, min(BM, rows_x - j * BM)};
+        });
     }
     if (e < CTRL_WORDS) {
         int v = 0;
