@@ -226,7 +226,7 @@ int moe_device_status(const void* ws, void* stream);
  * with the smallest predicted latency.  Nothing here touches a GPU: all pointers
  * are host pointers, the calls are synchronous and allocate only host memory.
  *
- * Hardware H: n_sm workers (SMs / CUs), p_peak FLOP/s, beta_hbm and beta_link
+ * Hardware H: n_sm workers (SMs / CUs, 2..1024), p_peak FLOP/s, beta_hbm and beta_link
  * (one direction) in bytes/s, w_sat = warps (waves) that saturate a bandwidth,
  * tau_sync seconds per tile for its scoreboard traffic, mu[i] = GEMM utilisation
  * with 8, 16, 32 warps per worker (the paper: 0.7, 0.65, 0.6; w_sat 1024; 2 us).

@@ -26,7 +26,7 @@ int warp_slot(int w) {
 }
 
 bool hw_ok(const moe_perf_hw_t& h) {
-    if (h.n_sm < 2 || h.w_sat < 1) return false;
+    if (h.n_sm < 2 || h.n_sm > 1024 || h.w_sat < 1) return false;   // the pair walk is O(n_sm^4 / 4096)
     if (!(h.p_peak > 0) || !(h.beta_hbm > 0) || !(h.beta_link > 0) || !(h.tau_sync >= 0)) return false;
     for (int i = 0; i < 3; ++i)
         if (!(h.mu[i] > 0)) return false;

@@ -115,6 +115,8 @@ def test_argument_checks():
         moe.moe_perf_model_eval(hw, moe.make_perf_problem(**model_problem(6, 4096, 7)), ok)   # 128 % 7 != 0
     with pytest.raises(moe.MoEError):
         moe.moe_perf_model_eval(moe.make_perf_hw(n_sm=132, p_peak=0.0, beta_hbm=1e12, beta_link=1e11), pr, ok)
+    with pytest.raises(moe.MoEError):   # more workers than the search is sized for
+        moe.moe_perf_model_search(moe.make_perf_hw(n_sm=1025, p_peak=1e14, beta_hbm=1e12, beta_link=1e11), pr)
     with pytest.raises(moe.MoEError):   # four workers: no valid configuration at all
         moe.moe_perf_model_search(moe.make_perf_hw(n_sm=4, p_peak=1e14, beta_hbm=1e12, beta_link=1e11), pr)
     lib = moe.load_library()
