@@ -151,14 +151,14 @@ __global__ void __launch_bounds__(1024) bwd_prologue_kernel(BwdParams p) {
         // tile), weight-gradient GEMMs over (output row tile, output column tile)
         const int nt_x = (rows_x + BM - 1) / BM;
         for_each_tile(lane, nt_x, p.nct_dh, [&](int j, int ct) {
-            ta[block_pos<false>(j, ct, nt_x, p.nct_dh)] =
+            ta[block_pos<true>(j, ct, nt_x, p.nct_dh)] =
                 Task{rt0 + j, task_code(B_DH, x, ct), r0 + j * BM, min(BM, rows_x - j * BM)};
         });
         for_each_tile(lane, p.mt_dwd, p.nt_dwd, [&](int mt, int nt) {
             ta[n_dh + block_pos<false>(mt, nt, p.mt_dwd, p.nt_dwd)] = Task{mt, task_code(B_DWD, x, nt), r0, rows_x};
         });
         for_each_tile(lane, nt_x, p.nct_dxp, [&](int j, int ct) {
-            tb[block_pos<false>(j, ct, nt_x, p.nct_dxp)] =
+            tb[block_pos<true>(j, ct, nt_x, p.nct_dxp)] =
                 Task{rt0 + j, task_code(B_DXP, x, ct), r0 + j * BM, min(BM, rows_x - j * BM)};
         });
         for_each_tile(lane, p.mt_dwgu, p.nt_dwgu, [&](int mt, int nt) {

@@ -183,10 +183,11 @@ __device__ __forceinline__ int fetch_finish(const PendingFetch f, int* ctrl, int
 // groups of kColGroup column tiles, inside a column group row groups of kRowGroup row tiles:
 // 32 consecutive entries cover 4 row tiles x 8 column tiles (12 operand streams) where a
 // row-major order covers 1 x 32 (33 streams: the weights of a 1024-row expert were fetched
-// four times).  Inside a 4 x 8 group the forward pass puts the row tiles innermost, so that
-// the tiles that share a weight tile are fetched back to back (measured 1 % faster on the
-// forward pass of the 512-row experts, 1 % slower on their backward pass, which keeps the
-// column tiles innermost).
+// four times).  Inside a 4 x 8 group the row-tile GEMMs (forward, dH, dXp) put the row tiles
+// innermost, so that the tiles that share a weight tile are fetched back to back (measured
+// 1 % on the forward pass and 0.7 % on the backward pass of 512-row experts); the
+// weight-gradient blocks, whose two operands are both row slabs of the expert, keep the column
+// tiles innermost (the other order cost 0.5 %).
 // block_pos() gives the entry of tile (j, ct); for_each_tile() hands every tile of the grid to
 // the lanes of one wave, 8 row tiles x 8 column tiles per round, without a division.
 constexpr int kColGroup = 8;   // 4 x 8 and 6 x 6 (rows x columns) measured within 1 % of 8 x 4
