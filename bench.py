@@ -78,7 +78,7 @@ def event_ms(fn, n, before=None):
 
 def measured_traffic(cfg_name, kernel):
     """HBM bytes per launch of `kernel` from the committed counter summary
-    (profiles/hbm_traffic_<workload>.txt, written by paper_2604_19241_amd.profile_summary
+    (profiles/hbm_traffic_<workload>.txt, written by profile_summary.py
     from a FETCH_SIZE and a WRITE_SIZE run scaled by the calibration copy), or None."""
     path = ROOT / "profiles" / f"hbm_traffic_{cfg_name.replace('-', '_')}.txt"
     if not path.exists():

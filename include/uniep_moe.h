@@ -15,12 +15,16 @@
  *   - All data pointers are DEVICE pointers (HIP global memory) unless a
  *     parameter is marked "host".  moe_shape_t / moe_routing_t / moe_opts_t
  *     structs themselves live in host memory.
- *   - The caller owns every buffer.  The library allocates nothing, keeps no
- *     state between calls, enqueues all work on `stream` (a hipStream_t passed
- *     as void*; NULL = the default stream) and never synchronises with the
+ *   - The caller owns every buffer.  The library allocates nothing and keeps no
+ *     data between calls (the only process-wide state is a per-device cache of
+ *     how many worker workgroups fit on the device, filled on first use under a
+ *     lock and never changed afterwards).  All work is enqueued on `stream` (a hipStream_t passed
+ *     as void*; NULL = the default stream) and no call synchronises with the
  *     host: the number of routed rows and all tile tables stay on the device.
  *   - Arrays are dense row-major.  bf16 tensors are passed as void*.
- *   - Outputs are overwritten, never accumulated into.
+ *   - Outputs are overwritten, never accumulated into, with one exception the
+ *     caller asks for: moe_opts_t.dw_accumulate = 1 adds the weight gradients
+ *     to fp32 buffers.
  *   - Return value: MOE_OK or a negative error code.  All argument, shape and
  *     workspace checks happen before anything is enqueued, so a failed call
  *     has no effect.
@@ -46,7 +50,7 @@ extern "C" {
 #define MOE_OK 0
 #define MOE_ERR_ARG (-1)       /* NULL or misaligned pointer */
 #define MOE_ERR_SHAPE (-2)     /* shape outside the limits above */
-#define MOE_ERR_WORKSPACE (-3) /* workspace / saved buffer too small */
+#define MOE_ERR_WORKSPACE (-3) /* ws_bytes too small (the size of `saved` is not passed and cannot be checked) */
 #define MOE_ERR_HIP (-4)       /* a HIP runtime call failed (launch, attribute) */
 #define MOE_ERR_DEVICE (-5)    /* reported by moe_device_status: a kernel gave up a bounded wait */
 
@@ -80,8 +84,16 @@ typedef struct {
     int32_t schedule; /* 0 = default (= 3), 1 = one persistent work-queue MegaKernel for every
                          task, 2 = staged: one launch per phase (same tile code; for profiling),
                          3 = one persistent MegaKernel for all GEMM tasks with scoreboard
-                         waits, then a second launch of the same kernel for the tail tasks
-                         (combine / dX), which may only start once every GEMM task is done */
+                         waits, then a plain grid kernel for the tail tasks (combine / dX:
+                         fwd_tail_kernel / bwd_tail_kernel, one workgroup per 16 tokens),
+                         which may only start once every GEMM task is done.
+                         Schedule 1 makes the tail tasks wait inside the kernel until EVERY
+                         worker has started and run out of GEMM work, so it needs all
+                         `workers` workgroups co-resident: the occupancy query that bounds
+                         `workers` cannot see kernels of other streams or processes, and if
+                         some worker never becomes resident the waits end at spin_limit_ms
+                         with MOE_ERR_DEVICE and partly written y / dx.  Schedules 0, 2, 3
+                         have no such precondition. */
     int32_t workers;  /* persistent workgroups; 0 = one per resident slot (never more than
                          can be co-resident: the deadlock-freedom condition of Section 3.1) */
     int32_t spin_limit_ms; /* bound on every scoreboard wait; 0 = 2000 ms.  A wait that
@@ -148,7 +160,11 @@ int moe_fused_forward(const moe_shape_t* shape, const void* x, const void* w_gat
  * dW_down[e] = h_e^T dO_e, dW_gate[e] = x_e^T dG_e, dW_up[e] = x_e^T dU_e, each
  * reduced over the expert's rows in row order (fixed by the token mapping, so
  * bitwise reproducible).  Experts with no rows get exact zeros.
- *   saved    the stash a forward call with the same inputs filled (required)
+ *   saved    the stash a forward call with the same inputs filled.  REQUIRED:
+ *            NULL returns MOE_ERR_ARG.  A backward pass that recomputes G, U and h
+ *            instead is not built: it would repeat two thirds of the forward
+ *            GEMM work inside the backward kernel to save a stash that costs
+ *            6 % of the forward pass's traffic to write.
  *   dx       [T,d] bf16;  dw_gate, dw_up [e_count,d,I] bf16;  dw_down [e_count,I,d] bf16
  *            (overwritten; with opts->dw_accumulate = 1: fp32, added to)
  *   dtopk_w  [T,k] fp32 = <dy[t], o[row(t,j)]> (0 for non-local slots), or NULL.
@@ -282,6 +298,17 @@ const char* moe_status_string(int code);
  * read, bytes written) is what the HBM byte counters of a profiler run are
  * scaled by.  Returns MOE_ERR_ARG for a NULL/misaligned pointer or size. */
 int moe_calibration_copy(void* dst, const void* src, size_t bytes, void* stream);
+
+/* Measurement aid, not part of the MoE path: `workgroups` workgroups of `waves` waves
+ * (1..8) each run `iters` rounds of 8 dependent-free v_mfma_f32_32x32x16_bf16 on operands
+ * taken from seed[0..1023] (device, any bit patterns of finite bf16 pairs).  What this
+ * reaches is the matrix-core ceiling under the power limit, the denominator the roofline
+ * fractions are compared with besides the published peak.
+ *   sink    device, 1 float (never written in practice)
+ *   clocks  device, 2 x int64: [0] shader clocks, [1] 100 MHz ticks that the first wave
+ *           of workgroup 0 spent in the loop: their ratio is the shader clock under load. */
+int moe_calibration_mfma(int32_t workgroups, int32_t waves, int32_t iters, const uint32_t* seed,
+                         float* sink, long long* clocks, void* stream);
 
 #ifdef __cplusplus
 }

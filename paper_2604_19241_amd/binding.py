@@ -22,7 +22,7 @@ MOE_ERR_ARG, MOE_ERR_SHAPE, MOE_ERR_WORKSPACE, MOE_ERR_HIP, MOE_ERR_DEVICE = -1,
 EXPORTS = ("moe_workspace_bytes", "moe_saved_layout", "moe_route", "moe_fused_forward",
            "moe_fused_backward", "moe_route_backward", "moe_global_map", "moe_device_status",
            "moe_status_string", "moe_calibration_copy", "moe_perf_model_eval",
-           "moe_perf_model_search")
+           "moe_perf_model_search", "moe_calibration_mfma")
 
 
 class MoEShape(ctypes.Structure):
@@ -147,6 +147,35 @@ def moe_route(shape: MoEShape, logits: torch.Tensor, ws: torch.Tensor | None = N
     _check(load_library().moe_route(ctypes.byref(shape), _ptr(logits), ctypes.byref(cs), _ptr(ws),
                                     ctypes.c_size_t(ws.numel()), _stream(dev)), "moe_route")
     return r
+
+
+def alloc_routing(shape: MoEShape, device) -> Routing:
+    T, k, ec = shape.T, shape.k, shape.e_count
+    return Routing(torch.empty((T, k), dtype=torch.int32, device=device),
+                   torch.empty((T, k), dtype=torch.float32, device=device),
+                   torch.empty(ec, dtype=torch.int32, device=device),
+                   torch.empty(ec + 1, dtype=torch.int32, device=device),
+                   torch.empty(T * k, dtype=torch.int32, device=device),
+                   torch.empty((T, k), dtype=torch.int32, device=device))
+
+
+def moe_calibration_mfma(workgroups: int, waves: int, iters: int, device="cuda") -> dict:
+    """Runs the dependent-free MFMA stream once and returns its shader clocks and 100 MHz ticks
+    (synchronises to read them).  The caller times the call itself for TFLOP/s."""
+    import numpy as np
+    rng = np.random.default_rng(3)
+    # pairs of bf16 values in +-[0.5, 2): random mantissas, two exponents, random signs
+    hi = 0x3F00 + rng.integers(0, 256, (1024, 2)) + (rng.integers(0, 2, (1024, 2)) << 15)
+    seed = torch.from_numpy((hi[:, 0] | (hi[:, 1] << 16)).astype(np.uint32).view(np.int32)).to(device)
+    sink = torch.zeros(1, dtype=torch.float32, device=device)
+    clocks = torch.zeros(2, dtype=torch.int64, device=device)
+    _check(load_library().moe_calibration_mfma(ctypes.c_int32(workgroups), ctypes.c_int32(waves),
+                                               ctypes.c_int32(iters), _ptr(seed), _ptr(sink),
+                                               _ptr(clocks), _stream(torch.device(device))),
+           "moe_calibration_mfma")
+    c = clocks.cpu().tolist()
+    return {"shader_clocks": int(c[0]), "ticks_100mhz": int(c[1]),
+            "flop": float(workgroups) * waves * iters * 8 * 32768.0}
 
 
 def moe_fused_forward(shape: MoEShape, x, w_gate, w_up, w_down, routing: Routing, y=None,

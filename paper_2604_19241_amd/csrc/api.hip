@@ -94,6 +94,43 @@ __global__ void __launch_bounds__(256) calibration_copy_kernel(uniep::u32x4_t* _
         __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
 }
 
+// Dependent-free bf16 MFMA stream with non-trivial operands: what the matrix pipes sustain
+// when nothing else runs (profiler and bench calibration of the matrix-core ceiling and of
+// the shader clock under that load).  clk[0] = shader clocks, clk[1] = 100 MHz ticks that the
+// first wave of workgroup 0 spent in the loop.
+__global__ void __launch_bounds__(512) calibration_mfma_kernel(int iters, const uint32_t* __restrict__ seed,
+                                                               float* __restrict__ sink, long long* clk) {
+    using namespace uniep;
+    u32x4_t ar, br;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        ar[i] = seed[(threadIdx.x * 4 + i) & 1023];
+        br[i] = seed[(threadIdx.x * 4 + i + 512) & 1023];
+    }
+    const bf16x8_t a = __builtin_bit_cast(bf16x8_t, ar), b = __builtin_bit_cast(bf16x8_t, br);
+    f32x16_t acc[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
+    const long long c0 = clock64(), w0 = wall_clock64();
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[j], 0, 0, 0);
+    }
+    const long long c1 = clock64(), w1 = wall_clock64();
+    float s = 0.f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) s += acc[j][v];
+    if (s == 0.12345f) sink[0] = s;   // keeps the accumulators alive
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        clk[0] = c1 - c0;
+        clk[1] = w1 - w0;
+    }
+}
+
 __global__ void clear_status_kernel(int* ws) { ws[uniep::CTRL_STATUS] = 0; }
 
 extern "C" {
@@ -105,6 +142,15 @@ int moe_calibration_copy(void* dst, const void* src, size_t bytes, void* stream)
     const int grid = (int)std::min<size_t>((n16 + 255) / 256, 256 * 16);
     hipLaunchKernelGGL(calibration_copy_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream,
                        (uniep::u32x4_t*)dst, (const uniep::u32x4_t*)src, n16);
+    return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
+}
+
+int moe_calibration_mfma(int32_t workgroups, int32_t waves, int32_t iters, const uint32_t* seed,
+                         float* sink, long long* clocks, void* stream) {
+    if (!seed || !sink || !clocks || ((uintptr_t)seed & 3) || ((uintptr_t)clocks & 7)) return MOE_ERR_ARG;
+    if (workgroups < 1 || workgroups > 65536 || waves < 1 || waves > 8 || iters < 1) return MOE_ERR_ARG;
+    hipLaunchKernelGGL(calibration_mfma_kernel, dim3(workgroups), dim3(64 * waves), 0, (hipStream_t)stream,
+                       iters, seed, sink, clocks);
     return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
 
@@ -251,7 +297,7 @@ const char* moe_status_string(int code) {
         case MOE_OK: return "ok";
         case MOE_ERR_ARG: return "bad argument (null or misaligned pointer, bad option)";
         case MOE_ERR_SHAPE: return "shape outside the supported limits";
-        case MOE_ERR_WORKSPACE: return "workspace or saved buffer too small";
+        case MOE_ERR_WORKSPACE: return "workspace too small";
         case MOE_ERR_HIP: return "HIP runtime call failed";
         case MOE_ERR_DEVICE: return "a kernel gave up a bounded scoreboard wait";
         default: return "unknown status";

@@ -19,6 +19,8 @@
 //   4  dX[t] = sum_j dXp[row(t,j)] in slot order; dtopk_w = <dY[t], o[row]>
 #include "tiles.hpp"
 
+#include <mutex>
+
 namespace uniep {
 
 enum BwdTask { B_DH = 0, B_DWD = 1, B_DXP = 2, B_DWGU = 3, B_DX = 4 };
@@ -464,20 +466,6 @@ __device__ __forceinline__ void dx_task(const BwdParams& p, int block) {
     }
 }
 
-#ifdef UNIEP_PROFILE_BWD   // timing experiments only: per-worker event trace {type, start, end, xcd}
-constexpr int kTraceEventsB = 160;
-__device__ long long g_trace_b[256][kTraceEventsB][4];
-#define TRACE_B(type) do { if (threadIdx.x == 0 && blockIdx.x < 256 && n_ev < kTraceEventsB) { \
-    g_trace_b[blockIdx.x][n_ev][0] = (type); g_trace_b[blockIdx.x][n_ev][1] = t_ev; \
-    g_trace_b[blockIdx.x][n_ev][2] = wall_clock64(); g_trace_b[blockIdx.x][n_ev][3] = home; } ++n_ev; } while (0)
-extern "C" int moe_debug_trace_bwd(long long* out) {
-    if (hipDeviceSynchronize() != hipSuccess) return MOE_ERR_HIP;
-    return hipMemcpyFromSymbol(out, HIP_SYMBOL(g_trace_b), sizeof(long long) * 256 * kTraceEventsB * 4) == hipSuccess
-               ? MOE_OK : MOE_ERR_HIP;
-}
-#else
-#define TRACE_B(type) do { } while (0)
-#endif
 
 // ------------------------------------------------------------- worker loop
 // ACC: the weight gradients are added to fp32 buffers (moe_opts_t.dw_accumulate).
@@ -499,15 +487,9 @@ __device__ __forceinline__ void bwd_worker_body(const BwdParams& p, int phase, c
         s_task = fetch_task(ctrl, pass, home, exhausted, use_lists, use_tail);
     }
     __syncthreads();
-#ifdef UNIEP_PROFILE_BWD
-    int n_ev = 0;
-#endif
     for (;;) {
         const int id = s_task;
         if (id == kFetchDone) break;
-#ifdef UNIEP_PROFILE_BWD
-        const long long t_ev = wall_clock64();
-#endif
         // issued behind the main loop of the task (see the forward worker)
         PendingFetch pf;
         pf.q = -1;
@@ -531,17 +513,14 @@ __device__ __forceinline__ void bwd_worker_body(const BwdParams& p, int phase, c
                     add_relaxed(p.flag_rt + task.idx, 1);
                     add_relaxed(p.flag_e + rt.expert, 1);
                 }
-                TRACE_B(B_DH + 16 * rt.rows);
             } else if (type == B_DWD) {
                 dwd_task<NW, ACC>(p, task_expert(task), task.idx, ct, task.row0, task.rows, smem, issue);
-                TRACE_B(B_DWD);
             } else if (type == B_DXP) {
                 if (threadIdx.x == 0) s_ok = wait_ge(p.flag_rt + task.idx, p.nct_dh, ctrl, p.spin_ticks);
                 __syncthreads();
                 if (s_ok) {
                     const RowTile rt = task_row_tile(task);
                     dxp_task<NW>(p, rt, ct, smem, issue);
-                    TRACE_B(B_DXP + 16 * rt.rows);
                 }
             } else {
                 const int e = task_expert(task);
@@ -550,7 +529,6 @@ __device__ __forceinline__ void bwd_worker_body(const BwdParams& p, int phase, c
                 if (threadIdx.x == 0) s_ok = wait_ge(p.flag_e + e, need, ctrl, p.spin_ticks);
                 __syncthreads();
                 if (s_ok) dwgu_task<NW, ACC>(p, e, task.idx, ct, task.row0, task.rows, smem, issue);
-                TRACE_B(B_DWGU);
             }
         } else {
             if (publishes && !arrived) {
@@ -565,9 +543,7 @@ __device__ __forceinline__ void bwd_worker_body(const BwdParams& p, int phase, c
             if (threadIdx.x == 0)
                 s_ok = wait_ge(ctrl + CTRL_DONE, ctrl[CTRL_NWAIT], ctrl, p.spin_ticks, CTRL_TAIL_WAIT_TICKS);
             __syncthreads();
-            TRACE_B(5);   // wait ahead of a tail task
             if (s_ok) dx_task<NW>(p, -1 - id);
-            TRACE_B(B_DX);
         }
         issue();           // tasks without a main loop (tail, skipped, given up)
         __syncthreads();
@@ -641,13 +617,15 @@ static BwdLayout bwd_layout(const moe_shape_t& s, int bm) {
 
 size_t bwd_workspace_bytes(const moe_shape_t& s) { return bwd_layout(s, 128).total; }   // 128-row tiles need the most tasks
 
-static int g_bwd_workers[32];
+static std::mutex g_bwd_workers_mu;
+static int g_bwd_workers[kMaxDevices * 4];   // filled on first use under the lock, constant afterwards
 
 template <int NW, bool ACC>
 static int bwd_resident_workers(int* out) {
     int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return MOE_ERR_HIP;
-    const int slot = ((dev & 7) * 2 + (NW == 8 ? 1 : 0)) * 2 + (ACC ? 1 : 0);
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return MOE_ERR_HIP;
+    const int slot = (dev * 2 + (NW == 8 ? 1 : 0)) * 2 + (ACC ? 1 : 0);
+    std::lock_guard<std::mutex> lock(g_bwd_workers_mu);
     if (g_bwd_workers[slot] == 0) {
         const void* fn = ACC ? (const void*)bwd_worker_acc_kernel<NW> : (const void*)bwd_worker_kernel<NW>;
         if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize,

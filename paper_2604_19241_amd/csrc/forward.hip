@@ -12,32 +12,15 @@
 // accumulators.
 #include "tiles.hpp"
 
+#include <mutex>
+
 namespace uniep {
 
 enum TaskType { TASK_GEMM1 = 0, TASK_GEMM2 = 1, TASK_COMBINE = 2 };
 
 // Where GEMM1 stages its A operand (the gathered rows of x): 1 = straight into registers,
 // 0 = through LDS with 128-byte coalesced row pieces.
-#ifndef UNIEP_GEMM1_A_DIRECT
-#define UNIEP_GEMM1_A_DIRECT 1
-#endif
 
-#ifdef UNIEP_PROFILE   // timing experiments only: 10 ns ticks per task type {fetch, wait, main, epilogue, count}
-__device__ unsigned long long g_prof[3][8];
-#define PROF_NOW() wall_clock64()
-#define PROF_ADD(type, slot, val) do { if (threadIdx.x == 0) atomicAdd(&g_prof[type][slot], (unsigned long long)(val)); } while (0)
-// per-worker event trace: [worker][event] = {type, start tick, end tick, xcd}
-constexpr int kTraceEvents = 96;
-__device__ long long g_trace[512][kTraceEvents][4];
-#define TRACE_EVENT(n, type, t0) do { if (threadIdx.x == 0 && blockIdx.x < 512 && (n) < kTraceEvents) { \
-    g_trace[blockIdx.x][n][0] = (type); g_trace[blockIdx.x][n][1] = (t0); g_trace[blockIdx.x][n][2] = wall_clock64(); \
-    int lq_ = 0; for (int q_ = 1; q_ < kQueues; ++q_) if (id >= ctrl[CTRL_QBASE + q_]) lq_ = q_; \
-    g_trace[blockIdx.x][n][3] = home + 16 * lq_; } ++(n); } while (0)
-#else
-#define TRACE_EVENT(n, type, t0) do { } while (0)
-#define PROF_NOW() 0ll
-#define PROF_ADD(type, slot, val) do { } while (0)
-#endif
 constexpr int kCombineTokens = 16;   // tokens per combine task (4 per wave)
 
 struct FwdParams {
@@ -165,31 +148,15 @@ __global__ void __launch_bounds__(1024) fwd_prologue_kernel(FwdParams p) {
 template <int NW, class Hook>
 __device__ __forceinline__ void gemm1_task(const FwdParams& p, const RowTile rt, int ct,
                                            char* smem, Hook after_mainloop) {
-    const long long t_start = PROF_NOW();
     typedef Geom<NW> G;
     const int d = p.s.d, I = p.s.I, k = p.s.k;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-#if UNIEP_GEMM1_A_DIRECT
     DirectRowLoader<false> al;   // dispatch = gather: each lane reads its token's row of x
     {
         const int m = min(wave * 32 + (lane & 31), rt.rows - 1);   // rows past the tile alias its last row
         const int tok = p.perm[rt.row0 + m] / k;
         al.rp = p.x + ((size_t)tok * d + (lane >> 5) * 32) * 2;
     }
-#else
-    typedef RowLoader<G::NT, G::BM, false> AL;   // dispatch = gather: 8 lanes read 128 bytes of a token's row of x
-    AL al;
-    al.init();
-    {
-        const int kc = tid & 7;
-#pragma unroll
-        for (int q = 0; q < AL::NP; ++q) {
-            const int m = min(AL::row(q), rt.rows - 1);   // rows past the tile alias its last row
-            const int tok = p.perm[rt.row0 + m] / k;
-            al.rp[q] = p.x + ((size_t)tok * d + kc * 8) * 2;
-        }
-    }
-#endif
     typedef StridedLoader<G::NT, 32> BL;
     BL bl;
     bl.init();
@@ -202,16 +169,8 @@ __device__ __forceinline__ void gemm1_task(const FwdParams& p, const RowTile rt,
         bl.bp = w + (((size_t)rt.expert * d + BL::TG::k0()) * I + hc) * 2;
     }
     f32x16_t acc[8];
-#if UNIEP_GEMM1_A_DIRECT
     mma_mainloop_direct<NW>(al, bl, d / BK, smem, wave * 32 < rt.rows, acc);
-#else
-    mma_mainloop<NW>(al, bl, d / BK, smem, wave * 32 < rt.rows, acc);
-#endif
     after_mainloop();
-    PROF_ADD(TASK_GEMM1, 2, PROF_NOW() - t_start);
-    PROF_ADD(TASK_GEMM1, 5, d / BK);
-    const long long t_main = PROF_NOW();
-    (void)t_main;
 
     // epilogue: SwiGLU on the accumulators; lanes (2q, 2q+1) trade halves so that
     // each ends with G and U of 4 consecutive h-columns.
@@ -239,13 +198,6 @@ __device__ __forceinline__ void gemm1_task(const FwdParams& p, const RowTile rt,
             if (p.gu) store_stream16(p.gu + (row * 2 * I + (odd ? I : 0) + gcol) * 2, pack_row8(acc, v));
         }
     }
-#ifdef UNIEP_PROFILE
-    if (rt.rows == G::BM) {
-        PROF_ADD(TASK_GEMM1, 0, 1);
-        PROF_ADD(TASK_GEMM1, 1, t_main - t_start);
-        PROF_ADD(TASK_GEMM1, 3, PROF_NOW() - t_main);
-    }
-#endif
 }
 
 // ------------------------------------------------------------- GEMM2 task
@@ -253,7 +205,6 @@ __device__ __forceinline__ void gemm1_task(const FwdParams& p, const RowTile rt,
 template <int NW, class Hook>
 __device__ __forceinline__ void gemm2_task(const FwdParams& p, const RowTile rt, int ct,
                                            char* smem, Hook after_mainloop) {
-    const long long t_start = PROF_NOW();
     typedef Geom<NW> G;
     const int d = p.s.d, I = p.s.I;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -274,8 +225,6 @@ __device__ __forceinline__ void gemm2_task(const FwdParams& p, const RowTile rt,
     f32x16_t acc[8];
     mma_mainloop_direct<NW>(al, bl, I / BK, smem, wave * 32 < rt.rows, acc);
     after_mainloop();
-    PROF_ADD(TASK_GEMM2, 2, PROF_NOW() - t_start);
-    PROF_ADD(TASK_GEMM2, 5, I / BK);
     const int col = n0 + (lane & 31) * 8;
     if (col < d) {
 #pragma unroll
@@ -376,13 +325,9 @@ fwd_worker_kernel(FwdParams p, int phase) {
         s_task = fetch_task(ctrl, pass, home, exhausted, use_lists, use_tail);
     }
     __syncthreads();
-    int n_ev = 0;
-    (void)n_ev;
     for (;;) {
         const int id = s_task;
         if (id == kFetchDone) break;
-        const long long t_ev = PROF_NOW();
-        (void)t_ev;
         // The cursor atomic of the next task is issued behind the main loop of this one: vector
         // memory results return in order, so an atomic issued ahead of a tile would hold back
         // the first loads of its wave by the atomic's round trip.
@@ -401,25 +346,16 @@ fwd_worker_kernel(FwdParams p, int phase) {
                 // staged launch: another phase's task, nothing to do
             } else if (type == TASK_GEMM1) {
                 const RowTile rt = task_row_tile(task);
-#ifdef UNIEP_PROFILE
-                if (rt.rows == Geom<NW>::BM) PROF_ADD(TASK_GEMM1, 4, PROF_NOW() - t_ev);
-                const long long t_g1 = PROF_NOW();
-#endif
                 gemm1_task<NW>(p, rt, ct, smem, issue);
                 wait_stores();
                 __syncthreads();   // the write-through h stores of every wave have completed
                 if (threadIdx.x == 0) add_relaxed(p.flag1 + task.idx, 1);
-#ifdef UNIEP_PROFILE
-                if (rt.rows == Geom<NW>::BM) PROF_ADD(TASK_GEMM1, 6, PROF_NOW() - t_g1);
-#endif
-                TRACE_EVENT(n_ev, TASK_GEMM1 + 16 * rt.rows, t_ev);
             } else {
                 if (threadIdx.x == 0) s_ok = wait_ge(p.flag1 + task.idx, p.nct1, ctrl, p.spin_ticks);
                 __syncthreads();
                 if (s_ok) {
                     const RowTile rt = task_row_tile(task);
                     gemm2_task<NW>(p, rt, ct, smem, issue);
-                    TRACE_EVENT(n_ev, TASK_GEMM2 + 16 * rt.rows, t_ev);
                 }
             }
         } else {
@@ -435,9 +371,7 @@ fwd_worker_kernel(FwdParams p, int phase) {
             if (threadIdx.x == 0)
                 s_ok = wait_ge(ctrl + CTRL_DONE, ctrl[CTRL_NWAIT], ctrl, p.spin_ticks, CTRL_TAIL_WAIT_TICKS);
             __syncthreads();
-            TRACE_EVENT(n_ev, 3, t_ev);   // wait before a tail task
             if (s_ok) combine_task<NW>(p, -1 - id);
-            TRACE_EVENT(n_ev, TASK_COMBINE, t_ev);
         }
         issue();           // tasks without a main loop (tail, skipped, given up)
         __syncthreads();   // every thread has read s_task / s_ok of this round
@@ -491,13 +425,17 @@ FwdLayout fwd_layout(const moe_shape_t& s, bool with_ho) {
 size_t fwd_workspace_bytes(const moe_shape_t& s) { return fwd_layout(s, true).total; }
 size_t fwd_ctrl_bytes(const moe_shape_t& s) { return fwd_layout(s, false).total; }
 
-static int g_workers[16];   // resident worker slots per device and tile height
+// Resident worker slots per device and tile height: the one piece of process-wide state,
+// filled on first use under a lock and constant afterwards.
+static std::mutex g_workers_mu;
+static int g_workers[kMaxDevices * 2];
 
 template <int NW>
 static int resident_workers(int* out) {
     int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return MOE_ERR_HIP;
-    const int slot = (dev & 7) * 2 + (NW == 8 ? 1 : 0);
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return MOE_ERR_HIP;
+    const int slot = dev * 2 + (NW == 8 ? 1 : 0);
+    std::lock_guard<std::mutex> lock(g_workers_mu);
     if (g_workers[slot] == 0) {
         if (hipFuncSetAttribute((const void*)fwd_worker_kernel<NW>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -575,21 +513,5 @@ int fwd_launch(const moe_shape_t& s, const void* x, const void* w_gate, const vo
 }
 
 
-#ifdef UNIEP_PROFILE
-extern "C" int moe_debug_prof(unsigned long long* out, int reset) {
-    if (hipDeviceSynchronize() != hipSuccess) return MOE_ERR_HIP;
-    if (reset == 2) {   // out receives the event trace of the last launch instead
-        return hipMemcpyFromSymbol(out, HIP_SYMBOL(g_trace), sizeof(long long) * 512 * kTraceEvents * 4) ==
-                       hipSuccess ? MOE_OK : MOE_ERR_HIP;
-    }
-    if (hipMemcpyFromSymbol(out, HIP_SYMBOL(g_prof), sizeof(unsigned long long) * 24) != hipSuccess)
-        return MOE_ERR_HIP;
-    if (reset) {
-        unsigned long long z[24] = {};
-        if (hipMemcpyToSymbol(HIP_SYMBOL(g_prof), z, sizeof(z)) != hipSuccess) return MOE_ERR_HIP;
-    }
-    return MOE_OK;
-}
-#endif
 
 }  // namespace uniep

@@ -5,9 +5,11 @@
 // [32w, 32w+32) and all 256 columns: 8 accumulators of
 // v_mfma_f32_32x32x16_bf16 (16 fp32 each, kept in AGPRs).  With NW = 8 the two
 // waves of a SIMD hide each other's LDS and global latency.
-// Both operands are staged through LDS as [row][k] with k contiguous, 64 k per
-// stage, rows padded to 144 bytes so that 16-byte fragment reads of
-// consecutive rows fall in distinct banks.  Two LDS stages: global loads of
+// The B operand (and, in the weight-gradient GEMMs, the A operand too) is staged
+// through LDS as [row][k] with k contiguous, 64 k per stage, rows padded to
+// 144 bytes so that the 16-byte fragment reads of consecutive rows fall in
+// distinct banks; the A operand of the row-tile GEMMs goes straight from global
+// memory into registers (DirectRowLoader).  Two LDS stages: global loads of
 // stage s+1 are in flight while stage s feeds the matrix cores.
 //
 // Column mapping of the B operand: the 256 tile columns are 32 chunks of 8
@@ -20,14 +22,6 @@
 #include "common.hpp"
 
 namespace uniep {
-
-// Timing experiments only: -DUNIEP_ALIAS_STAGE0 makes every K-stage re-read stage 0
-// (tiny memory footprint, wrong results) to separate memory stalls from issue limits.
-#ifdef UNIEP_ALIAS_STAGE0
-#define UNIEP_STAGE_OF(s) 0
-#else
-#define UNIEP_STAGE_OF(s) (s)
-#endif
 
 constexpr int BK = 64;
 constexpr int BN = 256;
@@ -86,7 +80,7 @@ struct RowLoader {
         if (part != 0) return;
 #pragma unroll
         for (int p = 0; p < NP; ++p)
-            reg[p] = *(const u32x4_t*)(rp[p] + (size_t)UNIEP_STAGE_OF(s) * (BK * 2));
+            reg[p] = *(const u32x4_t*)(rp[p] + (size_t)s * (BK * 2));
     }
     __device__ __forceinline__ void sstore_part(char* base, int part) {
         if (part != 0) return;
@@ -152,12 +146,8 @@ __device__ __forceinline__ void transpose_store(const u32x4_t (&in)[KR], char* d
 #pragma unroll
         for (int p = 0; p < KR / 2; ++p) {
             const uint32_t lo = in[2 * p][j >> 1], hi = in[2 * p + 1][j >> 1];
-#ifdef UNIEP_X_NOTRANS   // timing experiments only (wrong results)
-            o[p] = (j & 1) ? lo : hi;
-#else
             // one byte permute per word: {lo.hi16, hi.hi16} or {lo.lo16, hi.lo16}
             o[p] = (j & 1) ? __builtin_amdgcn_perm(hi, lo, 0x07060302u) : __builtin_amdgcn_perm(hi, lo, 0x05040100u);
-#endif
         }
         char* d = dst + j * row_stride;
         if (KR == 8) *(u32x4_t*)d = u32x4_t{o[0], o[1], o[2], o[3]};
@@ -192,10 +182,7 @@ struct StridedLoader {
     // the transpose needs all k-rows of the block: the whole stage moves in part 0
     __device__ __forceinline__ void gload_part(int s, int part) {
         if (part != 0) return;
-#ifdef UNIEP_X_NOBLOAD   // timing experiments only (wrong results)
-        if (s > 1) return;
-#endif
-        const char* p = bp + (size_t)UNIEP_STAGE_OF(s) * BK * ld_bytes;
+        const char* p = bp + (size_t)s * BK * ld_bytes;
 #pragma unroll
         for (int r = 0; r < TG::KR; ++r) reg[r] = *(const u32x4_t*)(p + r * ld_bytes);
     }
@@ -501,10 +488,7 @@ struct DirectRowLoader {
     u32x4_t frag[BK / 16];
 
     __device__ __forceinline__ void load(int s, int kk) {
-#ifdef UNIEP_X_NOALOAD   // timing experiments only (wrong results)
-        if (s > 0) return;
-#endif
-        frag[kk] = *(const u32x4_t*)(rp + (size_t)UNIEP_STAGE_OF(s) * (BK * 2) + kk * 16);
+        frag[kk] = *(const u32x4_t*)(rp + (size_t)s * (BK * 2) + kk * 16);
     }
     __device__ __forceinline__ bf16x8_t get(int kk) const {
         u32x4_t r = frag[kk];

@@ -1,8 +1,8 @@
 """Text summaries of rocprofv3 runs (rocpd sqlite output) for this library's kernels.
 
-  python -m paper_2604_19241_amd.profile_summary kernels  DIR OUT.txt --cmd "..."
-  python -m paper_2604_19241_amd.profile_summary counters DIR OUT.txt --cmd "..."
-  python -m paper_2604_19241_amd.profile_summary traffic  FETCH_DIR WRITE_DIR OUT.txt
+  python profile_summary.py kernels  DIR OUT.txt --cmd "..."
+  python profile_summary.py counters DIR OUT.txt --cmd "..."
+  python profile_summary.py traffic  FETCH_DIR WRITE_DIR OUT.txt
          --copy-bytes N --cmd "..." [--cmd "..."]
 
 `kernels` lists calls / total / average duration per kernel of a --kernel-trace run;

@@ -128,6 +128,17 @@ def test_calibration_copy_rejects_bad_arguments(lib):
     assert lib.moe_calibration_copy(256, 512, 0, None) == b.MOE_OK               # nothing to copy, nothing launched
 
 
+def test_calibration_mfma_rejects_bad_arguments(lib):
+    from paper_2604_19241_amd import binding as b
+    lib.moe_calibration_mfma.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p,
+                                         ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+    ok = (256, 8, 10, 0x1000, 0x1000, 0x1000, None)
+    for i, bad in ((0, 0), (1, 0), (1, 9), (2, 0), (3, None), (4, None), (5, None), (3, 0x1002), (5, 0x1004)):
+        args = list(ok)
+        args[i] = bad
+        assert lib.moe_calibration_mfma(*args) == b.MOE_ERR_ARG, (i, bad)
+
+
 def test_global_map_rejects_bad_arguments(lib):
     from paper_2604_19241_amd import binding as b
     lib.moe_global_map.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p,
