@@ -18,7 +18,8 @@
  *   - The caller owns every buffer.  The library allocates nothing and keeps no
  *     data between calls (the only process-wide state is a per-device cache of
  *     how many worker workgroups fit on the device, filled on first use under a
- *     lock and never changed afterwards).  All work is enqueued on `stream` (a hipStream_t passed
+ *     lock and never changed afterwards, and the file-scope scratch array of
+ *     moe_route_static).  All work is enqueued on `stream` (a hipStream_t passed
  *     as void*; NULL = the default stream) and no call synchronises with the
  *     host: the number of routed rows and all tile tables stay on the device.
  *   - Arrays are dense row-major.  bf16 tensors are passed as void*.
@@ -138,6 +139,20 @@ int moe_saved_layout(const moe_shape_t* shape, size_t* off_gu, size_t* off_h, si
  * positions, so it is identical on every run. */
 int moe_route(const moe_shape_t* shape, const float* logits, const moe_routing_t* out,
               void* ws, size_t ws_bytes, void* stream);
+
+/* moe_route for callers that cannot allocate or bring a workspace (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): same inputs, outputs
+ * and results as moe_route, but the per-chunk histogram lives in a file-scope device
+ * array of MOE_ROUTE_STATIC_SCRATCH_BYTES that every device the library runs on holds
+ * until the process ends.  The call allocates nothing and calls no allocating routine.
+ * Problems whose moe_workspace_bytes(...).route_ws exceeds that size return
+ * MOE_ERR_WORKSPACE before anything is enqueued.  Every call on a device shares that
+ * device's array: calls that overlap on one device (different streams, different host
+ * threads) race; calls ordered on one stream are safe.  Nothing in the array has to
+ * survive between calls, and every entry a call reads it has written itself. */
+#define MOE_ROUTE_STATIC_SCRATCH_BYTES (4u << 20)
+int moe_route_static(const moe_shape_t* shape, const float* logits, const moe_routing_t* out,
+                     void* stream);
 
 /* Forward: y[t] = sum_j topk_w[t,j] * o[row(t,j)] over the local slots of t in
  * slot order, fp32 accumulate, where for row r of local expert e holding token

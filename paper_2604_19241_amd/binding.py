@@ -22,7 +22,9 @@ MOE_ERR_ARG, MOE_ERR_SHAPE, MOE_ERR_WORKSPACE, MOE_ERR_HIP, MOE_ERR_DEVICE = -1,
 EXPORTS = ("moe_workspace_bytes", "moe_saved_layout", "moe_route", "moe_fused_forward",
            "moe_fused_backward", "moe_route_backward", "moe_global_map", "moe_device_status",
            "moe_status_string", "moe_calibration_copy", "moe_perf_model_eval",
-           "moe_perf_model_search", "moe_calibration_mfma")
+           "moe_perf_model_search", "moe_route_static", "moe_calibration_mfma")
+
+ROUTE_STATIC_SCRATCH_BYTES = 4 << 20   # MOE_ROUTE_STATIC_SCRATCH_BYTES
 
 
 class MoEShape(ctypes.Structure):
@@ -147,6 +149,17 @@ def moe_route(shape: MoEShape, logits: torch.Tensor, ws: torch.Tensor | None = N
     _check(load_library().moe_route(ctypes.byref(shape), _ptr(logits), ctypes.byref(cs), _ptr(ws),
                                     ctypes.c_size_t(ws.numel()), _stream(dev)), "moe_route")
     return r
+
+
+def moe_route_static(shape: MoEShape, logits: torch.Tensor, out: Routing) -> Routing:
+    """moe_route without a workspace: the library's file-scope scratch holds the histogram.
+    The caller brings the six output arrays (`out`), so the call itself allocates nothing."""
+    assert logits.is_cuda and logits.dtype == torch.float32 and logits.is_contiguous()
+    assert tuple(logits.shape) == (shape.T, shape.E)
+    cs = out.c_struct()
+    _check(load_library().moe_route_static(ctypes.byref(shape), _ptr(logits), ctypes.byref(cs),
+                                           _stream(logits.device)), "moe_route_static")
+    return out
 
 
 def alloc_routing(shape: MoEShape, device) -> Routing:

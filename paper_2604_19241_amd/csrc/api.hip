@@ -10,6 +10,8 @@ int route_backward_launch(const moe_shape_t& s, const int32_t* topk_idx, const f
                           const float* dtopk_w, float* dlogits, hipStream_t st);
 int route_launch(const moe_shape_t& s, const float* logits, const moe_routing_t& out, void* ws,
                  hipStream_t st);
+int route_static_launch(const moe_shape_t& s, const float* logits, const moe_routing_t& out,
+                        hipStream_t st);
 int global_map_launch(const moe_shape_t& s, int W, int rank, const moe_routing_t& r,
                       const int32_t* c_all, const moe_global_map_t& out, void* ws, hipStream_t st);
 size_t fwd_workspace_bytes(const moe_shape_t& s);
@@ -187,6 +189,17 @@ int moe_route(const moe_shape_t* shape, const float* logits, const moe_routing_t
     return route_launch(*shape, logits, *out, ws, (hipStream_t)stream);
 }
 
+int moe_route_static(const moe_shape_t* shape, const float* logits, const moe_routing_t* out,
+                     void* stream) {
+    int rc = check_shape(shape);
+    if (rc != MOE_OK) return rc;
+    rc = check_routing(out, shape->T);
+    if (rc != MOE_OK) return rc;
+    if (shape->T > 0 && (!logits || !aligned(logits, 4))) return MOE_ERR_ARG;
+    if (route_workspace_bytes(*shape) > kRouteStaticScratchBytes) return MOE_ERR_WORKSPACE;
+    return route_static_launch(*shape, logits, *out, (hipStream_t)stream);
+}
+
 int moe_fused_forward(const moe_shape_t* shape, const void* x, const void* w_gate, const void* w_up,
                       const void* w_down, const moe_routing_t* routing, void* y, void* saved,
                       void* ws, size_t ws_bytes, const moe_opts_t* opts, void* stream) {
@@ -297,7 +310,7 @@ const char* moe_status_string(int code) {
         case MOE_OK: return "ok";
         case MOE_ERR_ARG: return "bad argument (null or misaligned pointer, bad option)";
         case MOE_ERR_SHAPE: return "shape outside the supported limits";
-        case MOE_ERR_WORKSPACE: return "workspace too small";
+        case MOE_ERR_WORKSPACE: return "workspace too small (or the problem exceeds the static scratch of moe_route_static)";
         case MOE_ERR_HIP: return "HIP runtime call failed";
         case MOE_ERR_DEVICE: return "a kernel gave up a bounded scoreboard wait";
         default: return "unknown status";

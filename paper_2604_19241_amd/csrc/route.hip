@@ -11,6 +11,8 @@
 // ballots in lane order.  The result is therefore the same on every run.
 #include "common.hpp"
 
+#include <mutex>
+
 namespace uniep {
 
 constexpr int kChunk = 256;        // flat slots per wave-chunk (4 wave iterations)
@@ -391,6 +393,34 @@ int route_launch(const moe_shape_t& s, const float* logits, const moe_routing_t&
                            (int32_t*)out.perm, (int32_t*)out.inv_perm);
     }
     return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
+}
+
+// ------------------------------------------------ routing without a caller workspace
+// For callers that may not allocate (code under graph capture, tight serving loops): the
+// per-chunk histogram lives in a file-scope device array instead of a workspace argument.
+// Each device holds its own copy of the array at its own address, looked up once per
+// device (with that device current) and kept; host code never uses the array's name as an
+// address.  Every entry the kernels read is written earlier in the same call, so nothing
+// has to be cleared; calls that overlap on one device share the array and race.
+static __device__ __align__(256) unsigned char scratch[kRouteStaticScratchBytes];
+
+static std::mutex g_scratch_mu;
+static void* g_scratch_ptr[kMaxDevices];
+
+int route_static_launch(const moe_shape_t& s, const float* logits, const moe_routing_t& out,
+                        hipStream_t st) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return MOE_ERR_HIP;
+    void* ptr = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(g_scratch_mu);
+        ptr = g_scratch_ptr[dev];
+        if (!ptr) {
+            if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return MOE_ERR_HIP;
+            g_scratch_ptr[dev] = ptr;
+        }
+    }
+    return route_launch(s, logits, out, ptr, st);
 }
 
 }  // namespace uniep
