@@ -8,7 +8,7 @@ import torch
 
 import moe_synth
 import oracle
-from helpers import bits, rel_l2, say, scaled_inputs, to_f64
+from helpers import bits, check_elementwise, rel_l2, say, scaled_inputs, to_f64
 
 pytestmark = pytest.mark.gpu
 
@@ -51,6 +51,9 @@ def check_backward(cfg, seed, schedule, tile_rows, wscale):
         say(f"   vs oracle[{acc}]: " + " ".join(f"{k}={v:.2e}" for k, v in errs.items()))
         for key, v in errs.items():
             assert v <= GRAD_REL_L2, (key, v)
+        for key in KEYS:
+            check_elementwise(key, to_f64(g[key]), want[key])
+        check_elementwise("dtopk_w", to_f64(g["dtopk_w"]), want["dtopk_w"], whole_array_rms=True)
         # idle experts: exact zeros
         for e in np.nonzero(r["counts"] == 0)[0]:
             for key in ("dw_gate", "dw_up", "dw_down"):
@@ -84,6 +87,28 @@ def test_backward_idle_experts_and_skew():
     r = oracle.route(cfg.shape_dict(), inp["logits"].numpy())
     assert (r["counts"] == 0).any() and r["counts"].max() > 300
     check_backward(cfg, seed=5, schedule=1, tile_rows=0, wscale=4.0)
+
+
+@pytest.mark.parametrize("tile_rows", [128, 256])
+def test_backward_long_reduction(tile_rows):
+    """One expert with well over a thousand rows: the weight-gradient tiles reduce over many more
+    K stages than their index ring holds (its slots are reused and the clamped tail stages run),
+    compared element by element."""
+    cfg = moe_synth.small_config(T=1600, d=256, E=2, k=1, I=192)
+    inp = scaled_inputs(cfg, 41, 4.0)
+    inp["logits"][:, 0] += 0.9      # nearly every token picks expert 0
+    r = oracle.route(cfg.shape_dict(), inp["logits"].numpy())
+    assert r["counts"].max() >= 1500 and r["counts"].min() >= 1
+    say(f"[bwd] long reduction: rows per expert {r['counts'].tolist()}")
+    b = bits(inp, ("x", "dy", "w_gate", "w_up", "w_down"))
+    g, _ = gpu_fwd_bwd(cfg, inp, 0, tile_rows)
+    want = oracle.backward(cfg.shape_dict(), b["x"], b["dy"], b["w_gate"], b["w_up"], b["w_down"], r,
+                           round_bf16=True, acc="f32")
+    for key in KEYS:
+        err = rel_l2(to_f64(g[key]), want[key])
+        say(f"   {key} rel_l2={err:.2e}")
+        assert err <= GRAD_REL_L2, (key, err)
+        check_elementwise(key, to_f64(g[key]), want[key])
 
 
 def test_backward_is_bitwise_repeatable_and_schedule_independent():

@@ -1,17 +1,17 @@
 """Full-size parity at the benchmark's configurations, in the launch
 configuration bench.py times (default options: persistent MegaKernels).
 
-The oracle cannot run these sizes whole in seconds, so it computes sampled
-outputs one by one (token rows of y and dX, dtopk_w rows, whole weight-gradient
-matrices of sampled experts); properties that hold at any size cover the rest
-(bit-exact routing, exact zeros, bitwise repeatability)."""
+The oracle runs every configuration whole with fp32 accumulation (10-30 s of
+host time each), so every element of every output is compared; bit-exact
+routing, exact zeros and bitwise repeatability hold besides."""
 import numpy as np
 import pytest
 import torch
 
 import moe_synth
 import oracle
-from helpers import gpu_routing_as_np, max_abs, max_abs_beyond_ulp, rel_l2, say, to_f64
+from helpers import (C_RMS, check_elementwise, elementwise_ratio, gpu_routing_as_np, max_abs, max_abs_beyond_ulp,
+                     rel_l2, say, to_f64)
 
 pytestmark = pytest.mark.gpu
 
@@ -39,79 +39,74 @@ def run_gpu(cfg, inp, backward):
     return y, routing, grads, dev
 
 
-def sample_tokens(cfg, r, n, rng):
-    """Random tokens plus, when the share is partial, tokens with and without local slots."""
-    toks = set(int(t) for t in rng.integers(0, cfg.T, n))
-    local = (r["inv_perm"] >= 0).sum(1)
-    for want in (0, local.max()):
-        idx = np.nonzero(local == want)[0]
-        if idx.size:
-            toks.add(int(idx[0]))
-    return np.array(sorted(toks), np.int32)
-
-
 @pytest.mark.parametrize("cid", [2, 1, 3, 4])
-def test_fullsize_sampled_parity(cid):
+def test_fullsize_whole_output_parity(cid):
+    """Every element of y, and for the configurations with a backward pass every element of dX,
+    dtopk_w and of the three weight gradients of every local expert, against the oracle run whole
+    with fp32 accumulation (the benchmark spec's wording; seconds to tens of seconds of host time)."""
     cfg = moe_synth.CONFIGS[cid]
+    sh = cfg.shape_dict()
     say(f"[full] config {cid} {cfg.name}: generating inputs")
     inp = moe_synth.make_inputs(cfg)
-    logits = inp["logits"].numpy()
-    r = oracle.route(cfg.shape_dict(), logits)
+    r = oracle.route(sh, inp["logits"].numpy())
     say(f"[full] config {cid}: GPU route + forward{' + backward' if cfg.backward else ''}")
     y, routing, grads, dev = run_gpu(cfg, inp, cfg.backward)
     g = gpu_routing_as_np(routing)
     for key in ("topk_idx", "counts", "offsets", "perm", "inv_perm"):
         assert np.array_equal(g[key], r[key]), key
-    say(f"[full] config {cid}: load {moe_synth.histogram_summary(r['counts'])}")
+    counts = r["counts"]
+    say(f"[full] config {cid}: load {moe_synth.histogram_summary(counts)}")
 
-    rng = np.random.default_rng(100 + cid)
     keys = ("x", "w_gate", "w_up", "w_down") + (("dy",) if cfg.backward else ())
     b = {k: oracle.bf16_bits(inp[k]) for k in keys}
-    toks = sample_tokens(cfg, r, 24, rng)
-    say(f"[full] config {cid}: oracle forward on {len(toks)} sampled tokens")
-    want = oracle.forward_tokens(cfg.shape_dict(), b["x"], b["w_gate"], b["w_up"], b["w_down"], r,
-                                 toks)["y"]
-    got = to_f64(y[torch.from_numpy(toks).long().cuda()])
-    e_abs, e_rel, e_ulp = max_abs(got, want), rel_l2(got, want), max_abs_beyond_ulp(got, want)
-    say(f"   y: max_abs={e_abs:.3e} (beyond one bf16 ulp: {e_ulp:.3e}) rel_l2={e_rel:.3e} "
-        f"max|y|={np.abs(want).max():.2f}")
+    say(f"[full] config {cid}: oracle forward, whole ({oracle.threads()} threads)")
+    want = oracle.forward(sh, b["x"], b["w_gate"], b["w_up"], b["w_down"], r, round_bf16=True, acc="f32")["y"]
+    got = to_f64(y)
+    # the absolute bound applies where a bf16 ulp of the output stays below it (|y| <= 2.5);
+    # every element, larger ones included, is held to the element-wise relative bound
+    e_abs, e_rel, e_ulp = max_abs(got, want), rel_l2(got, want), max_abs_beyond_ulp(got, want, only_below=2.5)
+    say(f"   y [{cfg.T} x {cfg.d}]: max_abs={e_abs:.3e} (beyond one bf16 ulp, |y| <= 2.5: {e_ulp:.3e}) "
+        f"rel_l2={e_rel:.3e} max|y|={np.abs(want).max():.2f}")
     assert e_ulp <= MAX_ABS and e_rel <= REL_L2
+    check_elementwise("y", got, want)
     # tokens without a local slot give exact zeros
     none_local = np.nonzero((r["inv_perm"] >= 0).sum(1) == 0)[0]
     if none_local.size:
-        assert (y[torch.from_numpy(none_local[:64]).long().cuda()] == 0).all()
-
+        assert (y[torch.from_numpy(none_local).long().cuda()] == 0).all()
+    del got, want
     if not cfg.backward:
         return
-    say(f"[full] config {cid}: oracle backward on {len(toks)} sampled tokens")
-    wb = oracle.backward_tokens(cfg.shape_dict(), b["x"], b["dy"], b["w_gate"], b["w_up"],
-                                b["w_down"], r, toks)
-    idx = torch.from_numpy(toks).long().cuda()
-    e_dx = rel_l2(to_f64(grads["dx"][idx]), wb["dx"])
-    e_dw = rel_l2(to_f64(grads["dtopk_w"][idx]), wb["dtopk_w"])
-    say(f"   dx rel_l2={e_dx:.3e}  dtopk_w rel_l2={e_dw:.3e}")
-    assert e_dx <= GRAD_REL_L2 and e_dw <= GRAD_REL_L2
-    # whole weight-gradient matrices of sampled experts: a median-sized one, the
-    # smallest non-empty one, and (if any) an empty one
-    counts = r["counts"]
-    order = np.argsort(counts)
-    nonempty = order[counts[order] > 0]
-    picks = [int(nonempty[len(nonempty) // 2]), int(nonempty[0])]
-    if (counts == 0).any():
-        picks.append(int(np.nonzero(counts == 0)[0][0]))
-    picks = sorted(set(picks))
-    say(f"[full] config {cid}: oracle weight gradients of experts {picks} (rows {counts[picks].tolist()})")
-    we = oracle.backward_experts(cfg.shape_dict(), b["x"], b["dy"], b["w_gate"], b["w_up"],
-                                 b["w_down"], r, np.array(picks, np.int32))
-    for i, e in enumerate(picks):
-        for key in ("dw_gate", "dw_up", "dw_down"):
+
+    say(f"[full] config {cid}: oracle backward, whole")
+    wb = oracle.backward(sh, b["x"], b["dy"], b["w_gate"], b["w_up"], b["w_down"], r, round_bf16=True, acc="f32")
+    for key in ("dx", "dtopk_w"):
+        gg = to_f64(grads[key])
+        err = rel_l2(gg, wb[key])
+        say(f"   {key}: rel_l2={err:.3e}")
+        assert err <= GRAD_REL_L2, (key, err)
+        check_elementwise(key, gg, wb[key], whole_array_rms=(key == "dtopk_w"))
+    # every expert's weight gradients, expert by expert (the hottest, the smallest and the idle
+    # ones included; all eight task lists are covered because every expert is)
+    worst = {key: (0.0, -1) for key in ("dw_gate", "dw_up", "dw_down")}
+    worst_ratio = dict(worst)
+    for e in range(cfg.e_count):
+        for key in worst:
             gg = to_f64(grads[key][e])
             if counts[e] == 0:
                 assert (gg == 0).all(), (key, e)
-            else:
-                err = rel_l2(gg, we[key][i])
-                say(f"   expert {e} {key} rel_l2={err:.3e}")
-                assert err <= GRAD_REL_L2, (key, e, err)
+                continue
+            err = rel_l2(gg, wb[key][e])
+            assert err <= GRAD_REL_L2, (key, e, int(counts[e]), err)
+            ratio = elementwise_ratio(gg, wb[key][e])
+            assert ratio <= C_RMS[key], (key, e, int(counts[e]), ratio)
+            if err > worst[key][0]:
+                worst[key] = (err, e)
+            if ratio > worst_ratio[key][0]:
+                worst_ratio[key] = (ratio, e)
+    for key in worst:
+        say(f"   {key}: all {cfg.e_count} experts (rows {int(counts.min())}..{int(counts.max())}); worst rel_l2 "
+            f"{worst[key][0]:.3e} (expert {worst[key][1]}), worst element-wise excess {worst_ratio[key][0]:.3f} x 2^-8 "
+            f"rms(row) (expert {worst_ratio[key][1]}, bound {C_RMS[key]})")
 
 
 @pytest.mark.parametrize("cid", [2, 4])

@@ -10,7 +10,7 @@ import torch
 
 import moe_synth
 import oracle
-from helpers import bits, gpu_routing_as_np, max_abs_beyond_ulp, rel_l2, say, to_f64
+from helpers import bits, check_elementwise, gpu_routing_as_np, max_abs_beyond_ulp, rel_l2, say, to_f64
 from test_gpu_backward import GRAD_REL_L2, KEYS, gpu_fwd_bwd
 from test_gpu_forward import MAX_ABS, REL_L2
 
@@ -56,6 +56,7 @@ def test_model_shape_forward_backward(mid, tokens, e_start, e_count, tile_rows):
     e_ulp, e_rel = max_abs_beyond_ulp(yg, want["y"]), rel_l2(yg, want["y"])
     say(f"   y: max_abs beyond one bf16 ulp={e_ulp:.3e} rel_l2={e_rel:.3e}")
     assert e_ulp <= MAX_ABS and e_rel <= REL_L2
+    check_elementwise("y", yg, want["y"])
 
     wantb = oracle.backward(sh, b["x"], b["dy"], b["w_gate"], b["w_up"], b["w_down"], r,
                             round_bf16=True, acc="f32")
@@ -64,6 +65,9 @@ def test_model_shape_forward_backward(mid, tokens, e_start, e_count, tile_rows):
     say("   grads: " + " ".join(f"{k}={v:.2e}" for k, v in errs.items()))
     for key, v in errs.items():
         assert v <= GRAD_REL_L2, (key, v)
+    for key in KEYS:
+        check_elementwise(key, to_f64(g[key]), wantb[key])
+    check_elementwise("dtopk_w", to_f64(g["dtopk_w"]), wantb["dtopk_w"], whole_array_rms=True)
     for e in np.nonzero(r["counts"] == 0)[0]:
         for key in ("dw_gate", "dw_up", "dw_down"):
             assert (g[key][int(e)] == 0).all(), (key, e)
