@@ -17,7 +17,7 @@
 //   2  dXp = dG W_gate^T + dU W_up^T per row tile (one GEMM over k = 2I)
 //   3  dW_gate[e], dW_up[e] = x_e^T dG_e, x_e^T dU_e
 //   4  dX[t] = sum_j dXp[row(t,j)] in slot order; dtopk_w = <dY[t], o[row]>
-#include "tiles.hpp"
+#include "mma.hpp"
 
 #include <mutex>
 
@@ -53,10 +53,13 @@ struct BwdParams {
     float* row_w;
     char* dgu;   // [A,2I]
     char* dxp;   // [A,d]
-    float* dots; // [nct_dh][T*k] per dH column tile: sum over its columns of (dY W_down^T)[r][i] * h[r][i]
+    char* hw;    // [A,I]  gate * h, the row operand of dW_down (dO = gate * dY, with the gate moved to the other factor)
+    float* dots; // [4 * nct_dh][T*k] per dH column tile and wave column: sum over its 64 columns of (dY W_down^T)[r][i] * h[r][i]
     int nct_dh, nct_dxp;        // column tiles of phase 0 (256 of I) and phase 2 (256 of d)
     int mt_dwd, nt_dwd;         // dW_down tiles per expert: ceil(I/256) x ceil(d/256)
     int mt_dwgu, nt_dwgu;       // dW_gate/up tiles per expert: ceil(d/256) x ceil(I/128)
+    int n_dots;                 // partial sums per routed row: 4 * nct_dh
+    int bm;                     // rows per row tile (256, or 128)
     int workers;                // workgroups of the worker launch (the tail waits for all of them)
     long long spin_ticks;
 };
@@ -75,9 +78,10 @@ __global__ void __launch_bounds__(256) row_meta_kernel(BwdParams p) {
 }
 
 // One workgroup: row tiles, per-XCD task lists, cleared scoreboard.  List order
-// per XCD (experts i = 0..n-1 of that list): [dH_0, dWdown_0], [dH_1, dWdown_1],
-// [dXp_0, dWgu_0], [dH_2, dWdown_2], [dXp_1, dWgu_1], ...: the consumers of
-// expert i sit one expert behind its producers.
+// per XCD (experts i = 0..n-1 of that list): [dH_0], [dH_1], [dXp_0, dWgu_0, dWdown_0],
+// [dH_2], [dXp_1, dWgu_1, dWdown_1], ...: the consumers of expert i sit `lag` experts
+// behind its producers.  All three consumer kinds read what the dH tiles wrote
+// (dG|dU, and gate * h for dW_down).
 template <int BM>
 __global__ void __launch_bounds__(1024) bwd_prologue_kernel(BwdParams p) {
     __shared__ int32_t s_scan[kMaxExperts];
@@ -101,8 +105,8 @@ __global__ void __launch_bounds__(1024) bwd_prologue_kernel(BwdParams p) {
     }
     s_plan.cost[e] = cnt;
     s_scan[e] = nt;
-    s_ga[e] = (e < ec) ? nt * p.nct_dh + per_dwd : 0;
-    s_gb[e] = (e < ec) ? nt * p.nct_dxp + per_dwgu : 0;
+    s_ga[e] = (e < ec) ? nt * p.nct_dh : 0;
+    s_gb[e] = (e < ec) ? nt * p.nct_dxp + per_dwgu + per_dwd : 0;
     __syncthreads();
     for (int off = 1; off < kMaxExperts; off <<= 1) {
         const int32_t add = (e >= off) ? s_scan[e - off] : 0;
@@ -128,7 +132,7 @@ __global__ void __launch_bounds__(1024) bwd_prologue_kernel(BwdParams p) {
             base += s_qlen[q];
         }
         s_qbase[kQueues] = base;
-        s_lag = queue_lag(nrt * p.nct_dh + ec * per_dwd, ec);
+        s_lag = queue_lag(nrt * p.nct_dh, ec);
     }
     __syncthreads();
     if (e < ec) {
@@ -145,7 +149,7 @@ __global__ void __launch_bounds__(1024) bwd_prologue_kernel(BwdParams p) {
     __syncthreads();
     for (int x = e >> 6; x < ec; x += 16) {   // one wave writes the two blocks of an expert
         const int rt0 = s_rt0[x], lane = e & 63;
-        const int n_dh = s_ga[x] - per_dwd, n_dxp = s_gb[x] - per_dwgu;
+        const int n_dxp = s_gb[x] - per_dwgu - per_dwd;
         Task* ta = p.tasks + s_ta[x];
         Task* tb = p.tasks + s_tb[x];
         const int r0 = s_r0[x], rows_x = s_plan.cost[x];
@@ -156,15 +160,15 @@ __global__ void __launch_bounds__(1024) bwd_prologue_kernel(BwdParams p) {
             ta[block_pos<true>(j, ct, nt_x, p.nct_dh)] =
                 Task{rt0 + j, task_code(B_DH, x, ct), r0 + j * BM, min(BM, rows_x - j * BM)};
         });
-        for_each_tile(lane, p.mt_dwd, p.nt_dwd, [&](int mt, int nt) {
-            ta[n_dh + block_pos<false>(mt, nt, p.mt_dwd, p.nt_dwd)] = Task{mt, task_code(B_DWD, x, nt), r0, rows_x};
-        });
         for_each_tile(lane, nt_x, p.nct_dxp, [&](int j, int ct) {
             tb[block_pos<true>(j, ct, nt_x, p.nct_dxp)] =
                 Task{rt0 + j, task_code(B_DXP, x, ct), r0 + j * BM, min(BM, rows_x - j * BM)};
         });
         for_each_tile(lane, p.mt_dwgu, p.nt_dwgu, [&](int mt, int nt) {
             tb[n_dxp + block_pos<false>(mt, nt, p.mt_dwgu, p.nt_dwgu)] = Task{mt, task_code(B_DWGU, x, nt), r0, rows_x};
+        });
+        for_each_tile(lane, p.mt_dwd, p.nt_dwd, [&](int mt, int nt) {
+            tb[n_dxp + per_dwgu + block_pos<false>(mt, nt, p.mt_dwd, p.nt_dwd)] = Task{mt, task_code(B_DWD, x, nt), r0, rows_x};
         });
     }
     if (e < CTRL_WORDS) {
@@ -179,225 +183,248 @@ __global__ void __launch_bounds__(1024) bwd_prologue_kernel(BwdParams p) {
 }
 
 // ------------------------------------------------------------- phase 0: dH
-template <int NW, class Hook>
+// dH = dO W_down^T for one row tile and 256 columns of I, dO = gate * dY gathered on the fly:
+// the GEMM runs on the raw dY rows and the gate multiplies the fp32 accumulators, because the
+// unscaled product is also what dtopk_w needs: <dY[t], o[r]> = sum_i (dY[t] W_down^T)[i] h[r][i].
+// Epilogue: SwiGLU backward with the stashed G, U -> dG|dU; gate * h -> hw (dW_down's operand);
+// the partial dot products.
+template <class Hook>
 __device__ __forceinline__ void dh_task(const BwdParams& p, const RowTile rt, int ct, char* smem,
                                         Hook after_mainloop) {
-    typedef Geom<NW> G;
     const int d = p.s.d, I = p.s.I;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int kc = tid & 7;
-    // A = dY gathered; the gate multiplies the fp32 accumulators in the epilogue, which also
-    // needs the unscaled product: <dY[t], o[r]> = sum_i (dY[t] W_down^T)[i] * h[r][i].
-    DirectRowLoader<false> al;
-    float gate;   // of tile row wave*32 + lane%32
-    {
-        const int row = rt.row0 + min(wave * 32 + (lane & 31), rt.rows - 1);
-        al.rp = p.dy + ((size_t)p.row_tok[row] * d + (lane >> 5) * 32) * 2;
-        gate = p.row_w[row];
-    }
-    typedef RowLoader<G::NT, BN, false> BL;   // B rows are rows of W_down[e]: k (= d) contiguous
-    BL bl;
-    bl.init();
     const int n0 = ct * BN;
+    const Lane ln;
+    FragAddr fa;
+    frag_addresses<false, false>(fa, lds_addr(smem), ln);
+    KcLoader lb, la;
+    lb.n = KcLoader::blocks_for(ln, rt.rows);
 #pragma unroll
-    for (int q = 0; q < BL::NP; ++q) {
-        const int rho = BL::row(q);                       // LDS row j*32 + nb <-> column nb*8 + j
-        const int c = min(n0 + (rho & 31) * 8, I - 8) + (rho >> 5);
-        bl.rp[q] = p.w_down + (((size_t)rt.expert * I + c) * d + kc * 8) * 2;
+    for (int i = 0; i < 4; ++i) {
+        const int row = rt.row0 + min(KcGeom::row(ln, i), rt.rows - 1);   // rows past the tile alias its last row
+        lb.p[i] = p.dy + ((size_t)p.row_tok[row] * d + KcGeom::chunk(ln, i) * 8) * 2;
+        const int col = min(n0 + KcGeom::row(ln, i), I - 1);              // columns past I alias the last one
+        la.p[i] = p.w_down + (((size_t)rt.expert * I + col) * d + KcGeom::chunk(ln, i) * 8) * 2;
     }
-    f32x16_t acc[8];
-    mma_mainloop_direct<NW>(al, bl, d / BK, smem, wave * 32 < rt.rows, acc);
+    f32x16_t acc[4][2];
+    mma_tile<false, false>(lb, la, d / BK, rt.rows, smem, fa, acc);
     after_mainloop();
-    // epilogue: SwiGLU backward with the saved G, U of the same rows and columns
-    const int col = n0 + (lane & 31) * 8;
+    // epilogue, one row fragment (32 rows x the wave's 64 columns) at a time: the three outputs
+    // pass through three 4 KB pieces of the wave's LDS region and leave as 8-byte write-through
+    // stores, 16 neighbouring lanes on one 128-byte row segment
+    const Lane le;
+    const int lane = le.l, wn = le.wn;
     const bool want_dots = p.dtopk_w != nullptr;
+    WaveRepack<8> rg(smem, le), ru(smem + 4096, le), rh(smem + 8192, le);
+    const int rows_w = rt.rows - 128 * le.wm;      // rows of the tile inside this wave's 128
+    const int ocol = n0 + 64 * wn + 4 * rg.get8_piece();   // first of this lane's 4 columns on the way out
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-        const int m = wave * 32 + frag_row(v, lane);
-        const float gt = __shfl(gate, frag_row(v, lane));
+    for (int tf = 0; tf < 4; ++tf) {
+        const int m = acc_row(le, tf);
+        const float gt = p.row_w[rt.row0 + min(m, rt.rows - 1)];
         float dot = 0.f;
-        if (col < I && m < rt.rows) {
-            const size_t base = ((size_t)(rt.row0 + m) * 2 * I + col) * 2;
-            const u32x4_t gv = *(const u32x4_t*)(p.gu + base);
-            const u32x4_t uv = *(const u32x4_t*)(p.gu + base + (size_t)I * 2);
-            u32x4_t hv = zero4();   // the h that GEMM2 multiplied (bf16), not silu(g) * u of the rounded g, u
-            if (want_dots) hv = *(const u32x4_t*)(p.h + ((size_t)(rt.row0 + m) * I + col) * 2);
-            float dg[8], du[8];
+        const size_t row = (size_t)(rt.row0 + min(m, rt.rows - 1));
 #pragma unroll
-            for (int f = 0; f < 8; ++f) {
-                const float g = (f & 1) ? bf16_hi(gv[f >> 1]) : bf16_lo(gv[f >> 1]);
-                const float u = (f & 1) ? bf16_hi(uv[f >> 1]) : bf16_lo(uv[f >> 1]);
-                const float raw = acc[f][v];
-                const float dh = gt * raw;
-                const float sg = sigmoid_f(g);
-                const float silu = g * sg;
-                dot += raw * ((f & 1) ? bf16_hi(hv[f >> 1]) : bf16_lo(hv[f >> 1]));
-                du[f] = dh * silu;
-                dg[f] = dh * u * (sg * (1.f + g * (1.f - sg)));
-            }
-            u32x4_t dgp, dup;
+        for (int af = 0; af < 2; ++af)
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                dgp[q] = pack_bf16x2(dg[2 * q], dg[2 * q + 1]);
-                dup[q] = pack_bf16x2(du[2 * q], du[2 * q + 1]);
+            for (int vg = 0; vg < 2; ++vg) {
+                const int col = min(n0 + acc_col8(le, af, vg), I - 8);   // pieces past I alias a valid one, never stored
+                const size_t base = (row * 2 * I + col) * 2;
+                const u32x4_t gv = *(const u32x4_t*)(p.gu + base);
+                const u32x4_t uv = *(const u32x4_t*)(p.gu + base + (size_t)I * 2);
+                // the h that GEMM2 multiplied (bf16), not silu(g) * u of the rounded g, u
+                const u32x4_t hv = *(const u32x4_t*)(p.h + (row * I + col) * 2);
+                const bool live = m < rt.rows && n0 + acc_col8(le, af, vg) < I;
+                float dg[8], du[8], hs[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float g = (e & 1) ? bf16_hi(gv[e >> 1]) : bf16_lo(gv[e >> 1]);
+                    const float u = (e & 1) ? bf16_hi(uv[e >> 1]) : bf16_lo(uv[e >> 1]);
+                    const float hh = (e & 1) ? bf16_hi(hv[e >> 1]) : bf16_lo(hv[e >> 1]);
+                    const float raw = acc[tf][af][8 * vg + e];
+                    const float dh = gt * raw;
+                    const float sg = sigmoid_f(g);
+                    if (live) dot += raw * hh;
+                    hs[e] = gt * hh;
+                    du[e] = dh * (g * sg);
+                    dg[e] = dh * u * (sg * (1.f + g * (1.f - sg)));
+                }
+                u32x4_t dgp, dup, hwp;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    dgp[q] = pack_bf16x2(dg[2 * q], dg[2 * q + 1]);
+                    dup[q] = pack_bf16x2(du[2 * q], du[2 * q + 1]);
+                    hwp[q] = pack_bf16x2(hs[2 * q], hs[2 * q + 1]);
+                }
+                const int pi = 4 * af + 2 * vg + le.hf;
+                rg.put(le.l31, pi, dgp);
+                ru.put(le.l31, pi, dup);
+                rh.put(le.l31, pi, hwp);
             }
-            // consumed by dXp / dW_gate / dW_up tiles on any XCD
-            store_wt16(p.dgu + base, dgp);
-            store_wt16(p.dgu + base + (size_t)I * 2, dup);
+        // consumed by dXp / dW tiles on any XCD
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int r = 32 * tf + rg.get8_row(j);
+            if (r < rows_w && ocol < I) {
+                const size_t orow = (size_t)(rt.row0 + 128 * le.wm + r);
+                store_wt8(p.dgu + (orow * 2 * I + ocol) * 2, rg.get8(j));
+                store_wt8(p.dgu + (orow * 2 * I + I + ocol) * 2, ru.get8(j));
+                store_wt8(p.hw + (orow * I + ocol) * 2, rh.get8(j));
+            }
         }
         if (want_dots) {
-            // the 32 lanes of a half hold the 256 columns of row m: fixed butterfly order
-#pragma unroll
-            for (int off = 16; off >= 1; off >>= 1) dot += __shfl_xor(dot, off);
-            if ((lane & 31) == 0 && m < rt.rows)
-                p.dots[(size_t)ct * ((size_t)p.s.T * p.s.k) + rt.row0 + m] = dot;
+            // the two lane halves hold the wave's 64 columns of row m between them
+            dot += __shfl_xor(dot, 32);
+            if (lane < 32 && m < rt.rows)
+                p.dots[(size_t)(ct * 4 + wn) * ((size_t)p.s.T * p.s.k) + rt.row0 + m] = dot;
         }
     }
 }
 
 // ------------------------------------------------------------- phase 2: dXp
-template <int NW, class Hook>
+// dXp = dG W_gate^T + dU W_up^T for one row tile and 256 columns of d: one GEMM over k = 2I whose
+// column operand switches from the rows of W_gate to the rows of W_up half way.
+template <class Hook>
 __device__ __forceinline__ void dxp_task(const BwdParams& p, const RowTile rt, int ct, char* smem,
                                         Hook after_mainloop) {
-    typedef Geom<NW> G;
     const int d = p.s.d, I = p.s.I;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int kc = tid & 7;
-    DirectRowLoader<false> al;
-    {
-        const int row = rt.row0 + min(wave * 32 + (lane & 31), rt.rows - 1);
-        al.rp = p.dgu + ((size_t)row * 2 * I + (lane >> 5) * 32) * 2;
-    }
-    typedef SplitRowLoader<G::NT, BN> BL;   // k < I: row of W_gate[e][c], k >= I: row of W_up[e][c]
-    BL bl;
-    bl.init();
     const int n0 = ct * BN;
+    const Lane ln;
+    FragAddr fa;
+    frag_addresses<false, false>(fa, lds_addr(smem), ln);
+    KcLoader lb;
+    KcSplitLoader la;
+    lb.n = KcLoader::blocks_for(ln, rt.rows);
 #pragma unroll
-    for (int q = 0; q < BL::NP; ++q) {
-        const int rho = BL::row(q);
-        const int c = min(n0 + (rho & 31) * 8, d - 8) + (rho >> 5);
-        bl.rp[q] = p.w_gate + (((size_t)rt.expert * d + c) * I + kc * 8) * 2;
+    for (int i = 0; i < 4; ++i) {
+        const int row = rt.row0 + min(KcGeom::row(ln, i), rt.rows - 1);
+        lb.p[i] = p.dgu + ((size_t)row * 2 * I + KcGeom::chunk(ln, i) * 8) * 2;
+        const int c = min(n0 + KcGeom::row(ln, i), d - 1);
+        la.p[i] = p.w_gate + (((size_t)rt.expert * d + c) * I + KcGeom::chunk(ln, i) * 8) * 2;
     }
-    bl.delta = (long long)(p.w_up - p.w_gate);
-    bl.switch_stage = I / BK;
-    f32x16_t acc[8];
-    mma_mainloop_direct<NW>(al, bl, 2 * I / BK, smem, wave * 32 < rt.rows, acc);
+    la.left = I / BK;
+    la.delta = (long long)(p.w_up - p.w_gate) - (long long)I * 2;
+    f32x16_t acc[4][2];
+    mma_tile<false, false>(lb, la, 2 * I / BK, rt.rows, smem, fa, acc);
     after_mainloop();
-    const int col = n0 + (lane & 31) * 8;
-    if (col < d) {
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int m = wave * 32 + frag_row(v, lane);
-            if (m < rt.rows)
-                store_stream16(p.dxp + ((size_t)(rt.row0 + m) * d + col) * 2, pack_row8(acc, v));
-        }
-    }
+    char* obase = p.dxp + ((size_t)rt.row0 * d + n0) * 2;
+    store_subtile_bf16(acc, smem, rt.rows, d - n0, [&](int row, int col, u32x4_t v) {
+        store_stream16(obase + ((size_t)row * d + col) * 2, v);
+    });
 }
 
 // Weight gradients added to an fp32 gradient buffer (a training loop's main gradient) instead
-// of written as bf16: q[0..8) += the lane's 8 consecutive columns of accumulator element v.
+// of written as bf16: q[0..8) += the lane's 8 consecutive columns 8 vg .. 8 vg + 7.
 // Every element belongs to exactly one tile, so the read-modify-write needs no atomic and the
 // sum does not depend on the schedule.
-__device__ __forceinline__ void accumulate_row8(float* q, const f32x16_t (&acc)[8], int v) {
+__device__ __forceinline__ void accumulate8(float* q, const f32x16_t& a, int vg) {
     typedef __attribute__((ext_vector_type(4))) float f32x4_t;
-    f32x4_t a = ((const f32x4_t*)q)[0], b = ((const f32x4_t*)q)[1];
-    a += f32x4_t{acc[0][v], acc[1][v], acc[2][v], acc[3][v]};
-    b += f32x4_t{acc[4][v], acc[5][v], acc[6][v], acc[7][v]};
-    __builtin_nontemporal_store(a, (f32x4_t*)q);
-    __builtin_nontemporal_store(b, (f32x4_t*)q + 1);
+    f32x4_t lo = ((const f32x4_t*)q)[0], hi = ((const f32x4_t*)q)[1];
+    lo += f32x4_t{a[8 * vg], a[8 * vg + 1], a[8 * vg + 2], a[8 * vg + 3]};
+    hi += f32x4_t{a[8 * vg + 4], a[8 * vg + 5], a[8 * vg + 6], a[8 * vg + 7]};
+    __builtin_nontemporal_store(lo, (f32x4_t*)q);
+    __builtin_nontemporal_store(hi, (f32x4_t*)q + 1);
 }
 
 // ------------------------------------------------------------- phase 1: dW_down
-// dW_down[e][i][c] = sum over the expert's rows r (ascending) of h[r][i] * dO[r][c].
-// Output tile: 32*NW rows of I by 256 columns of d.
-template <int NW, bool ACC, class Hook>
+// dW_down[e][i][c] = sum over the expert's rows r (ascending) of (gate_r h[r][i]) * dY[tok_r][c].
+// Output tile: 256 rows of I by 256 columns of d; both operands have k = r as their memory row.
+template <bool ACC, class Hook>
 __device__ __forceinline__ void dwd_task(const BwdParams& p, int e, int mt, int nt, int r0, int cnt,
                                          char* smem, Hook after_mainloop) {
-    typedef Geom<NW> G;
     const int d = p.s.d, I = p.s.I;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    typedef StridedLoaderK<G::NT, 4 * NW> AL;
-    AL al;
-    al.init();
-    al.ld_bytes = (size_t)I * 2;
-    al.K = cnt;
-    al.bp = p.h + ((size_t)r0 * I + min(mt * G::BM + AL::TG::chunk() * 8, I - 8)) * 2;
-    typedef GatherStridedLoader<G::NT, 32, true> BL;
-    BL bl;
-    bl.init();
-    bl.ld_bytes = (size_t)d * 2;
-    bl.row_tok = p.row_tok;
-    bl.row_w = p.row_w;
-    bl.row0 = r0;
-    bl.K = cnt;
-    bl.ring = smem + G::SMEM;
-    bl.src = p.dy + (size_t)min(nt * BN + BL::TG::chunk() * 8, d - 8) * 2;
-    f32x16_t acc[8];
-    mma_mainloop<NW>(al, bl, (cnt + BK - 1) / BK, smem, true, acc);
-    after_mainloop();
-    const int col = nt * BN + (lane & 31) * 8;
-    if (col < d) {
+    const int m0 = mt * BMAX, n0 = nt * BN;
+    const Lane ln;
+    FragAddr fa;
+    frag_addresses<true, true>(fa, lds_addr(smem), ln);
+    KsTailLoader lb;
+    KsGatherLoader la;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int m = mt * G::BM + tr_tile_row<NW>(wave * 32 + frag_row(v, lane));
-            if (m < I) {
-                if (ACC) {
-                    if (cnt > 0) accumulate_row8((float*)p.dw_down + ((size_t)e * I + m) * d + col, acc, v);
-                } else {
-                    store_stream16(p.dw_down + (((size_t)e * I + m) * d + col) * 2, pack_row8(acc, v));
-                }
+    for (int i = 0; i < 2; ++i) {
+        lb.p[i] = p.hw + (((size_t)r0 + KsGeom::krow(ln, i)) * I + min(m0 + KsGeom::chunk(ln, i) * 8, I - 8)) * 2;
+        la.coloff[i] = (uint32_t)min(n0 + KsGeom::chunk(ln, i) * 8, d - 8) * 2u;
+    }
+    lb.k0 = KsGeom::krow(ln, 0);
+    lb.ld_bytes = (long long)I * 2;
+    lb.K = cnt;
+    la.init(ln, p.dy, (long long)d * 2, p.row_tok + r0, cnt);
+    f32x16_t acc[4][2];
+    mma_tile<true, true>(lb, la, (cnt + BK - 1) / BK, min(BMAX, I - m0), smem, fa, acc);
+    after_mainloop();
+    if (ACC) {
+        const Lane le;
+#pragma unroll
+        for (int tf = 0; tf < 4; ++tf) {
+            const int m = m0 + acc_row(le, tf);
+            if (m < I && cnt > 0) {
+#pragma unroll
+                for (int af = 0; af < 2; ++af)
+#pragma unroll
+                    for (int vg = 0; vg < 2; ++vg) {
+                        const int col = n0 + acc_col8(le, af, vg);
+                        if (col < d) accumulate8((float*)p.dw_down + ((size_t)e * I + m) * d + col, acc[tf][af], vg);
+                    }
             }
         }
+    } else {
+        char* obase = p.dw_down + (((size_t)e * I + m0) * d + n0) * 2;
+        store_subtile_bf16(acc, smem, I - m0, d - n0, [&](int row, int col, u32x4_t v) {
+            store_stream16(obase + ((size_t)row * d + col) * 2, v);
+        });
     }
 }
 
 // ------------------------------------------------------------- phase 3: dW_gate, dW_up
 // dW_gate[e][c][i] = sum_r x[tok(r)][c] * dG[r][i]; dW_up likewise with dU.
-// Output tile: 32*NW rows of d by 128 columns of I, for both matrices at once.
-// B-tile chunk nb: even -> 8 columns of dG, odd -> the same 8 columns of dU.
-template <int NW, bool ACC, class Hook>
+// Output tile: 256 rows of d by 128 columns of I, for both matrices at once: column fragment 0
+// of a wave holds dG columns, fragment 1 the same dU columns.
+template <bool ACC, class Hook>
 __device__ __forceinline__ void dwgu_task(const BwdParams& p, int e, int mt, int nt, int r0, int cnt,
                                           char* smem, Hook after_mainloop) {
-    typedef Geom<NW> G;
     const int d = p.s.d, I = p.s.I;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    typedef GatherStridedLoader<G::NT, 4 * NW, false> AL;
-    AL al;
-    al.init();
-    al.ld_bytes = (size_t)d * 2;
-    al.row_tok = p.row_tok;
-    al.row_w = p.row_w;
-    al.row0 = r0;
-    al.K = cnt;
-    al.ring = smem + G::SMEM;
-    al.src = p.x + (size_t)min(mt * G::BM + AL::TG::chunk() * 8, d - 8) * 2;
-    typedef StridedLoaderK<G::NT, 32> BL;
-    BL bl;
-    bl.init();
-    bl.ld_bytes = (size_t)I * 4;
-    bl.K = cnt;
-    {
-        const int cb = BL::TG::chunk();
-        bl.bp = p.dgu + ((size_t)r0 * 2 * I + ((cb & 1) ? I : 0) + min(nt * 128 + (cb >> 1) * 8, I - 8)) * 2;
-    }
-    f32x16_t acc[8];
-    mma_mainloop<NW>(al, bl, (cnt + BK - 1) / BK, smem, true, acc);
-    after_mainloop();
-    const int nb = lane & 31;
-    const int icol = nt * 128 + (nb >> 1) * 8;
-    char* dst = (nb & 1) ? p.dw_up : p.dw_gate;
-    if (icol < I) {
+    const int m0 = mt * BMAX, n0i = nt * (BN / 2);
+    const Lane ln;
+    FragAddr fa;
+    frag_addresses<true, true>(fa, lds_addr(smem), ln);
+    KsGatherLoader lb;
+    KsTailLoader la;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int m = mt * G::BM + tr_tile_row<NW>(wave * 32 + frag_row(v, lane));
-            if (m < d) {
-                if (ACC) {
-                    if (cnt > 0) accumulate_row8((float*)dst + ((size_t)e * d + m) * I + icol, acc, v);
-                } else {
-                    store_stream16(dst + (((size_t)e * d + m) * I + icol) * 2, pack_row8(acc, v));
-                }
+    for (int i = 0; i < 2; ++i) {
+        lb.coloff[i] = (uint32_t)min(m0 + KsGeom::chunk(ln, i) * 8, d - 8) * 2u;
+        const int c = KsGeom::chunk(ln, i);
+        const int icol = min(n0i + 32 * (c >> 3) + 8 * (c & 3), I - 8);
+        la.p[i] = p.dgu + (((size_t)r0 + KsGeom::krow(ln, i)) * 2 * I + (((c >> 2) & 1) ? I : 0) + icol) * 2;
+    }
+    la.k0 = KsGeom::krow(ln, 0);
+    la.ld_bytes = (long long)2 * I * 2;
+    la.K = cnt;
+    lb.init(ln, p.x, (long long)d * 2, p.row_tok + r0, cnt);
+    f32x16_t acc[4][2];
+    mma_tile<true, true>(lb, la, (cnt + BK - 1) / BK, min(BMAX, d - m0), smem, fa, acc);
+    after_mainloop();
+    if (ACC) {
+        const Lane le;
+#pragma unroll
+        for (int tf = 0; tf < 4; ++tf) {
+            const int m = m0 + acc_row(le, tf);
+            if (m < d && cnt > 0) {
+#pragma unroll
+                for (int af = 0; af < 2; ++af)
+#pragma unroll
+                    for (int vg = 0; vg < 2; ++vg) {
+                        const int icol = n0i + 32 * le.wn + 16 * vg + 8 * le.hf;
+                        if (icol < I)
+                            accumulate8((float*)(af ? p.dw_up : p.dw_gate) + ((size_t)e * d + m) * I + icol, acc[tf][af], vg);
+                    }
             }
         }
+    } else {
+        // the wave's 64 columns are 32 columns of dW_gate and the same 32 of dW_up: pieces 0..3 | 4..7
+        const size_t ebase = ((size_t)e * d + m0) * I;
+        store_subtile_bf16(acc, smem, d - m0, BN, [&](int row, int col, u32x4_t v) {
+            const int pc = (col >> 3) & 7;
+            const int icol = n0i + 32 * (col >> 6) + 8 * (pc & 3);
+            if (icol < I) store_stream16(((pc & 4) ? p.dw_up : p.dw_gate) + (ebase + (size_t)row * I + icol) * 2, v);
+        });
     }
 }
 
@@ -455,12 +482,12 @@ __device__ __forceinline__ void dx_task(const BwdParams& p, int block) {
             if (two) store_stream16(p.dx + ((size_t)t * d + c1) * 2, o1);
         }
         if (want_dots && lane < k) {
-            // dtopk_w[t][j] = <dY[t], o[row]>: the partial sums of the row's dH column tiles,
-            // added in column-tile order; 0 for a slot whose expert is not local
+            // dtopk_w[t][j] = <dY[t], o[row]>: the partial sums of the row's dH column tiles (four
+            // per tile, one per wave column), added in column order; 0 for a slot whose expert is not local
             const int r = p.inv_perm[(size_t)t * k + lane];
             float s = 0.f;
             if (r >= 0)
-                for (int ct = 0; ct < p.nct_dh; ++ct) s += p.dots[(size_t)ct * ((size_t)T * k) + r];
+                for (int ct = 0; ct < p.n_dots; ++ct) s += p.dots[(size_t)ct * ((size_t)T * k) + r];
             p.dtopk_w[(size_t)t * k + lane] = s;
         }
     }
@@ -469,7 +496,7 @@ __device__ __forceinline__ void dx_task(const BwdParams& p, int block) {
 
 // ------------------------------------------------------------- worker loop
 // ACC: the weight gradients are added to fp32 buffers (moe_opts_t.dw_accumulate).
-template <int NW, bool ACC>
+template <bool ACC>
 __device__ __forceinline__ void bwd_worker_body(const BwdParams& p, int phase, char* smem) {
     __shared__ int s_task;
     __shared__ int s_ok;
@@ -500,35 +527,42 @@ __device__ __forceinline__ void bwd_worker_body(const BwdParams& p, int phase, c
             issued = true;
         };
         if (id >= 0) {
-            const Task task = p.tasks[id];
+            // the task is the same for every lane: keep its fields in scalar registers
+            Task task = p.tasks[id];
+            task.idx = rfl(task.idx);
+            task.code = rfl(task.code);
+            task.row0 = rfl(task.row0);
+            task.rows = rfl(task.rows);
             const int type = task_type(task), ct = task_ct(task);
             if (phase >= 0 && type != phase) {
                 // staged launch: another phase's task
             } else if (type == B_DH) {
                 const RowTile rt = task_row_tile(task);
-                dh_task<NW>(p, rt, ct, smem, issue);
+                dh_task(p, rt, ct, smem, issue);
                 wait_stores();
                 __syncthreads();   // the write-through dG|dU stores of every wave have completed
                 if (threadIdx.x == 0) {
                     add_relaxed(p.flag_rt + task.idx, 1);
                     add_relaxed(p.flag_e + rt.expert, 1);
                 }
-            } else if (type == B_DWD) {
-                dwd_task<NW, ACC>(p, task_expert(task), task.idx, ct, task.row0, task.rows, smem, issue);
             } else if (type == B_DXP) {
                 if (threadIdx.x == 0) s_ok = wait_ge(p.flag_rt + task.idx, p.nct_dh, ctrl, p.spin_ticks);
                 __syncthreads();
                 if (s_ok) {
                     const RowTile rt = task_row_tile(task);
-                    dxp_task<NW>(p, rt, ct, smem, issue);
+                    dxp_task(p, rt, ct, smem, issue);
                 }
             } else {
+                // weight-gradient tiles read what ALL dH tiles of the expert wrote (dG|dU, gate * h):
+                // its row tiles times the dH column tiles
                 const int e = task_expert(task);
-                // all dH tiles of the expert: its row tiles times the dH column tiles
-                const int need = (task.rows + Geom<NW>::BM - 1) / Geom<NW>::BM * p.nct_dh;
+                const int need = (task.rows + p.bm - 1) / p.bm * p.nct_dh;
                 if (threadIdx.x == 0) s_ok = wait_ge(p.flag_e + e, need, ctrl, p.spin_ticks);
                 __syncthreads();
-                if (s_ok) dwgu_task<NW, ACC>(p, e, task.idx, ct, task.row0, task.rows, smem, issue);
+                if (s_ok) {
+                    if (type == B_DWD) dwd_task<ACC>(p, e, task.idx, ct, task.row0, task.rows, smem, issue);
+                    else dwgu_task<ACC>(p, e, task.idx, ct, task.row0, task.rows, smem, issue);
+                }
             }
         } else {
             if (publishes && !arrived) {
@@ -543,7 +577,7 @@ __device__ __forceinline__ void bwd_worker_body(const BwdParams& p, int phase, c
             if (threadIdx.x == 0)
                 s_ok = wait_ge(ctrl + CTRL_DONE, ctrl[CTRL_NWAIT], ctrl, p.spin_ticks, CTRL_TAIL_WAIT_TICKS);
             __syncthreads();
-            if (s_ok) dx_task<NW>(p, -1 - id);
+            if (s_ok) dx_task<8>(p, -1 - id);
         }
         issue();           // tasks without a main loop (tail, skipped, given up)
         __syncthreads();
@@ -561,17 +595,15 @@ __device__ __forceinline__ void bwd_worker_body(const BwdParams& p, int phase, c
     }
 }
 
-template <int NW>
-__global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
+__global__ void __launch_bounds__(kMmaThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
 bwd_worker_kernel(BwdParams p, int phase) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    bwd_worker_body<NW, false>(p, phase, smem);
+    bwd_worker_body<false>(p, phase, smem);
 }
-template <int NW>
-__global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
+__global__ void __launch_bounds__(kMmaThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
 bwd_worker_acc_kernel(BwdParams p, int phase) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    bwd_worker_body<NW, true>(p, phase, smem);
+    bwd_worker_body<true>(p, phase, smem);
 }
 
 // dX (and dtopk_w) as a plain grid launch behind the GEMM MegaKernel, one workgroup per block
@@ -584,20 +616,20 @@ __global__ void __launch_bounds__(64 * NW) bwd_tail_kernel(BwdParams p) {
 // ------------------------------------------------------------------ host side
 
 struct BwdLayout {
-    size_t ctrl, flag_rt, flag_e, tasks, row_tok, row_w, dgu, dxp, dots, total;
+    size_t ctrl, flag_rt, flag_e, tasks, row_tok, row_w, dgu, dxp, hw, dots, total;
     int max_rt, nct_dh, nct_dxp, mt_dwd, nt_dwd, mt_dwgu, nt_dwgu;
 };
 
-static BwdLayout bwd_layout(const moe_shape_t& s, int bm) {
+static BwdLayout bwd_layout(const moe_shape_t& s) {
     BwdLayout L;
     const size_t A_cap = (size_t)s.T * s.k;
-    L.max_rt = (int)((A_cap + 127) / 128) + s.e_count;
+    L.max_rt = (int)((A_cap + 127) / 128) + s.e_count;   // 128-row tiles need the most entries
     L.nct_dh = (s.I + BN - 1) / BN;
     L.nct_dxp = (s.d + BN - 1) / BN;
-    L.mt_dwd = (s.I + bm - 1) / bm;
-    L.nt_dwd = (s.d + 255) / 256;
-    L.mt_dwgu = (s.d + bm - 1) / bm;
-    L.nt_dwgu = (s.I + 127) / 128;
+    L.mt_dwd = (s.I + BMAX - 1) / BMAX;
+    L.nt_dwd = (s.d + BN - 1) / BN;
+    L.mt_dwgu = (s.d + BMAX - 1) / BMAX;
+    L.nt_dwgu = (s.I + BN / 2 - 1) / (BN / 2);
     const size_t max_tasks = (size_t)L.max_rt * (L.nct_dh + L.nct_dxp) +
                              (size_t)s.e_count * (L.mt_dwd * L.nt_dwd + L.mt_dwgu * L.nt_dwgu) +
                              (s.T + kDxTokens - 1) / kDxTokens;
@@ -610,33 +642,31 @@ static BwdLayout bwd_layout(const moe_shape_t& s, int bm) {
     L.row_w = off;   off = align_up(off + A_cap * sizeof(float), 256);
     L.dgu = off;     off = align_up(off + A_cap * 2 * s.I * 2, 256);
     L.dxp = off;     off = align_up(off + A_cap * s.d * 2, 256);
-    L.dots = off;    off = align_up(off + (size_t)L.nct_dh * A_cap * sizeof(float), 256);
+    L.hw = off;      off = align_up(off + A_cap * s.I * 2, 256);
+    L.dots = off;    off = align_up(off + (size_t)4 * L.nct_dh * A_cap * sizeof(float), 256);
     L.total = off;
     return L;
 }
 
-size_t bwd_workspace_bytes(const moe_shape_t& s) { return bwd_layout(s, 128).total; }   // 128-row tiles need the most tasks
+size_t bwd_workspace_bytes(const moe_shape_t& s) { return bwd_layout(s).total; }
 
 static std::mutex g_bwd_workers_mu;
-static int g_bwd_workers[kMaxDevices * 4];   // filled on first use under the lock, constant afterwards
+static int g_bwd_workers[kMaxDevices * 2];   // filled on first use under the lock, constant afterwards
 
-template <int NW, bool ACC>
+template <bool ACC>
 static int bwd_resident_workers(int* out) {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return MOE_ERR_HIP;
-    const int slot = (dev * 2 + (NW == 8 ? 1 : 0)) * 2 + (ACC ? 1 : 0);
+    const int slot = dev * 2 + (ACC ? 1 : 0);
     std::lock_guard<std::mutex> lock(g_bwd_workers_mu);
     if (g_bwd_workers[slot] == 0) {
-        const void* fn = ACC ? (const void*)bwd_worker_acc_kernel<NW> : (const void*)bwd_worker_kernel<NW>;
-        if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                Geom<NW>::SMEM + kIdxRingBytes) != hipSuccess)
+        const void* fn = ACC ? (const void*)bwd_worker_acc_kernel : (const void*)bwd_worker_kernel;
+        if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kMmaSmem) != hipSuccess)
             return MOE_ERR_HIP;
         int per_cu = 0, cus = 0;
         const hipError_t occ = ACC
-            ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, bwd_worker_acc_kernel<NW>, Geom<NW>::NT,
-                                                           Geom<NW>::SMEM + kIdxRingBytes)
-            : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, bwd_worker_kernel<NW>, Geom<NW>::NT,
-                                                           Geom<NW>::SMEM + kIdxRingBytes);
+            ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, bwd_worker_acc_kernel, kMmaThreads, kMmaSmem)
+            : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, bwd_worker_kernel, kMmaThreads, kMmaSmem);
         if (occ != hipSuccess) return MOE_ERR_HIP;
         if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
             return MOE_ERR_HIP;
@@ -647,40 +677,39 @@ static int bwd_resident_workers(int* out) {
     return MOE_OK;
 }
 
-template <int NW, bool ACC>
+template <bool ACC>
 static void launch_worker(const BwdParams& p, int workers, int phase, hipStream_t st) {
     if (ACC)
-        hipLaunchKernelGGL(bwd_worker_acc_kernel<NW>, dim3(workers), dim3(Geom<NW>::NT),
-                           Geom<NW>::SMEM + kIdxRingBytes, st, p, phase);
+        hipLaunchKernelGGL(bwd_worker_acc_kernel, dim3(workers), dim3(kMmaThreads), kMmaSmem, st, p, phase);
     else
-        hipLaunchKernelGGL(bwd_worker_kernel<NW>, dim3(workers), dim3(Geom<NW>::NT),
-                           Geom<NW>::SMEM + kIdxRingBytes, st, p, phase);
+        hipLaunchKernelGGL(bwd_worker_kernel, dim3(workers), dim3(kMmaThreads), kMmaSmem, st, p, phase);
 }
 
-template <int NW, bool ACC>
-static int bwd_launch_nw(BwdParams& p, const moe_opts_t& opts, hipStream_t st) {
+template <int BM, bool ACC>
+static int bwd_launch_bm(BwdParams& p, const moe_opts_t& opts, hipStream_t st) {
     int resident = 0;
-    int rc = bwd_resident_workers<NW, ACC>(&resident);
+    int rc = bwd_resident_workers<ACC>(&resident);
     if (rc != MOE_OK) return rc;
     const int workers = opts.workers > 0 ? min(opts.workers, resident) : resident;
     p.workers = workers;
+    p.bm = BM;
     const int A_cap = p.s.T * p.s.k;
     if (A_cap > 0)
         hipLaunchKernelGGL(row_meta_kernel, dim3((A_cap + 255) / 256), dim3(256), 0, st, p);
-    hipLaunchKernelGGL(bwd_prologue_kernel<Geom<NW>::BM>, dim3(1), dim3(1024), 0, st, p);
+    hipLaunchKernelGGL(bwd_prologue_kernel<BM>, dim3(1), dim3(1024), 0, st, p);
     if (opts.schedule == 2) {
-        for (int phase = 0; phase < 5; ++phase) launch_worker<NW, ACC>(p, workers, phase, st);
+        for (int phase = 0; phase < 5; ++phase) launch_worker<ACC>(p, workers, phase, st);
     } else if (opts.schedule != 1) {   // 0 (default) and 3: GEMM MegaKernel, then the tail tasks
-        launch_worker<NW, ACC>(p, workers, -2, st);
+        launch_worker<ACC>(p, workers, -2, st);
         const int n_tail = (p.s.T + kDxTokens - 1) / kDxTokens;
         if (n_tail > 0 && !opts.skip_tail) {
             if (p.s.k <= 8)
-                hipLaunchKernelGGL((bwd_tail_kernel<NW, 8>), dim3(n_tail), dim3(Geom<NW>::NT), 0, st, p);
+                hipLaunchKernelGGL((bwd_tail_kernel<8, 8>), dim3(n_tail), dim3(kMmaThreads), 0, st, p);
             else
-                hipLaunchKernelGGL((bwd_tail_kernel<NW, kMaxTopK>), dim3(n_tail), dim3(Geom<NW>::NT), 0, st, p);
+                hipLaunchKernelGGL((bwd_tail_kernel<8, kMaxTopK>), dim3(n_tail), dim3(kMmaThreads), 0, st, p);
         }
     } else {
-        launch_worker<NW, ACC>(p, workers, -1, st);
+        launch_worker<ACC>(p, workers, -1, st);
     }
     return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
@@ -689,7 +718,7 @@ int bwd_launch(const moe_shape_t& s, const void* dy, const void* x, const void* 
                const void* w_up, const void* w_down, const moe_routing_t& r, const char* gu,
                const char* h, const char* o, void* dx, void* dw_gate, void* dw_up, void* dw_down,
                float* dtopk_w, char* ws, const moe_opts_t& opts, int nw, hipStream_t st) {
-    const BwdLayout L = bwd_layout(s, 32 * nw);
+    const BwdLayout L = bwd_layout(s);
     BwdParams p;
     p.s = s;
     p.dy = (const char*)dy;
@@ -717,7 +746,9 @@ int bwd_launch(const moe_shape_t& s, const void* dy, const void* x, const void* 
     p.row_w = (float*)(ws + L.row_w);
     p.dgu = ws + L.dgu;
     p.dxp = ws + L.dxp;
+    p.hw = ws + L.hw;
     p.dots = (float*)(ws + L.dots);
+    p.n_dots = 4 * L.nct_dh;
     p.nct_dh = L.nct_dh;
     p.nct_dxp = L.nct_dxp;
     p.mt_dwd = L.mt_dwd;
@@ -727,8 +758,8 @@ int bwd_launch(const moe_shape_t& s, const void* dy, const void* x, const void* 
     const int ms = opts.spin_limit_ms > 0 ? opts.spin_limit_ms : 2000;
     p.spin_ticks = (long long)ms * 100000ll;
     if (opts.dw_accumulate)
-        return nw == 4 ? bwd_launch_nw<4, true>(p, opts, st) : bwd_launch_nw<8, true>(p, opts, st);
-    return nw == 4 ? bwd_launch_nw<4, false>(p, opts, st) : bwd_launch_nw<8, false>(p, opts, st);
+        return nw == 4 ? bwd_launch_bm<128, true>(p, opts, st) : bwd_launch_bm<256, true>(p, opts, st);
+    return nw == 4 ? bwd_launch_bm<128, false>(p, opts, st) : bwd_launch_bm<256, false>(p, opts, st);
 }
 
 }  // namespace uniep

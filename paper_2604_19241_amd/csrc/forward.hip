@@ -10,7 +10,7 @@
 // written to HBM; the scoreboard that remains orders GEMM1 -> GEMM2 per row
 // tile and GEMM2 -> combine.  SwiGLU runs in the GEMM1 epilogue on the fp32
 // accumulators.
-#include "tiles.hpp"
+#include "mma.hpp"
 
 #include <mutex>
 
@@ -143,97 +143,118 @@ __global__ void __launch_bounds__(1024) fwd_prologue_kernel(FwdParams p) {
 
 // ------------------------------------------------------------- GEMM1 task
 // h[row0.., ct*128 .. +128) = silu(x_e W_gate) * (x_e W_up) for one row tile.
-// B-tile chunk nb: even -> 8 gate columns, odd -> the same 8 up columns, so the
-// lanes 2q and 2q+1 hold G and U of the same columns.
-template <int NW, class Hook>
+// Tile rows = the tile's tokens (their rows of x fetched through the permutation: the dispatch);
+// tile columns = 128 gate columns and the same 128 up columns, arranged so that column fragment
+// 0 of a wave holds gate columns and fragment 1 the same up columns: G and U of one h element
+// sit in the same lane and accumulator element.
+template <class Hook>
 __device__ __forceinline__ void gemm1_task(const FwdParams& p, const RowTile rt, int ct,
                                            char* smem, Hook after_mainloop) {
-    typedef Geom<NW> G;
     const int d = p.s.d, I = p.s.I, k = p.s.k;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    DirectRowLoader<false> al;   // dispatch = gather: each lane reads its token's row of x
-    {
-        const int m = min(wave * 32 + (lane & 31), rt.rows - 1);   // rows past the tile alias its last row
-        const int tok = p.perm[rt.row0 + m] / k;
-        al.rp = p.x + ((size_t)tok * d + (lane >> 5) * 32) * 2;
-    }
-    typedef StridedLoader<G::NT, 32> BL;
-    BL bl;
-    bl.init();
     const int n0h = ct * (BN / 2);
-    {
-        const int nb = BL::TG::chunk();
-        const int hc = min(n0h + (nb >> 1) * 8, I - 8);   // chunks past I alias the last chunk
-        const char* w = (nb & 1) ? p.w_up : p.w_gate;
-        bl.ld_bytes = (size_t)I * 2;
-        bl.bp = w + (((size_t)rt.expert * d + BL::TG::k0()) * I + hc) * 2;
+    const Lane ln;
+    FragAddr fa;
+    frag_addresses<true, false>(fa, lds_addr(smem), ln);
+    KcLoader lb;
+    KsLoader la;
+    lb.n = KcLoader::blocks_for(ln, rt.rows);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int m = min(KcGeom::row(ln, i), rt.rows - 1);   // rows past the tile alias its last row
+        const int tok = p.perm[rt.row0 + m] / k;
+        lb.p[i] = p.x + ((size_t)tok * d + KcGeom::chunk(ln, i) * 8) * 2;
+        const int c = KsGeom::chunk(ln, i);                    // tile column chunk: (wave column, gate|up, 8-column piece)
+        const int hc = min(n0h + 32 * (c >> 3) + 8 * (c & 3), I - 8);   // chunks past I alias the last chunk
+        const char* w = ((c >> 2) & 1) ? p.w_up : p.w_gate;
+        la.p[i] = w + (((size_t)rt.expert * d + KsGeom::krow(ln, i)) * I + hc) * 2;
     }
-    f32x16_t acc[8];
-    mma_mainloop_direct<NW>(al, bl, d / BK, smem, wave * 32 < rt.rows, acc);
+    la.step = (long long)BK * I * 2;
+    f32x16_t acc[4][2];
+    mma_tile<true, false>(lb, la, d / BK, rt.rows, smem, fa, acc);
     after_mainloop();
 
-    // epilogue: SwiGLU on the accumulators; lanes (2q, 2q+1) trade halves so that
-    // each ends with G and U of 4 consecutive h-columns.
-    const int nb = lane & 31;
-    const bool odd = lane & 1;
-    const int hcol = n0h + 4 * nb;              // first of this lane's 4 h-columns
-    const int gcol = n0h + (nb >> 1) * 8;       // first of the 8 G (even) / U (odd) columns
-    const bool col_ok = gcol < I;
+    // epilogue.  The wave's sub-tile is 128 rows x (32 gate columns | the same 32 up columns).
+    // First the G|U stash, through the wave's LDS region so that 4 neighbouring lanes store 64
+    // contiguous bytes; then h = silu(G) * U on the accumulators, out the same way in 8-byte
+    // write-through pieces (8 lanes per 64-byte row segment): GEMM2 tiles on any XCD read it.
+    const Lane le;
+    const int l31 = le.l31, hf = le.hf;
+    const int wm = le.wm, wn = le.wn;
+    const int hc0 = n0h + 32 * wn;        // first h column of this wave
+    const int rows_w = rt.rows - 128 * wm; // rows of the tile inside this wave's 128
+    if (p.gu) {
+        WaveRepack<8> rp(smem, le);
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-        const int m = wave * 32 + frag_row(v, lane);
-        float hv[4];
+        for (int tf = 0; tf < 4; ++tf)
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const float mine_lo = acc[q][v], mine_hi = acc[q + 4][v];
-            const float recv = dpp_swap_pair(odd ? mine_lo : mine_hi);
-            const float g = odd ? recv : mine_lo;
-            const float u = odd ? mine_hi : recv;
-            hv[q] = g * sigmoid_f(g) * u;
+            for (int af = 0; af < 2; ++af)
+#pragma unroll
+                for (int vg = 0; vg < 2; ++vg) rp.put(32 * tf + l31, 4 * af + 2 * vg + hf, pack8(acc[tf][af], vg));
+        const int pc = rp.get_piece();                       // 0..3: G pieces, 4..7: U pieces
+        const int col = hc0 + 8 * (pc & 3);
+        char* gbase = p.gu + ((size_t)(rt.row0 + 128 * wm) * 2 * I + ((pc & 4) ? I : 0) + col) * 2;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const int row = rp.get_row(j);
+            const u32x4_t v = rp.get(j);
+            if (row < rows_w && col < I) store_stream16(gbase + (size_t)row * 2 * I * 2, v);
         }
-        if (m < rt.rows && col_ok) {
-            const size_t row = (size_t)(rt.row0 + m);
-            u32x2_t hp = {pack_bf16x2(hv[0], hv[1]), pack_bf16x2(hv[2], hv[3])};
-            store_wt8(p.h + (row * I + hcol) * 2, hp);   // consumed by GEMM2 tiles on any XCD
-            if (p.gu) store_stream16(p.gu + (row * 2 * I + (odd ? I : 0) + gcol) * 2, pack_row8(acc, v));
+    }
+    {
+        WaveRepack<4> rp(smem, le);
+#pragma unroll
+        for (int tf = 0; tf < 4; ++tf)
+#pragma unroll
+            for (int vg = 0; vg < 2; ++vg) {
+                float hv[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float g = acc[tf][0][8 * vg + e], u = acc[tf][1][8 * vg + e];
+                    hv[e] = g * sigmoid_f(g) * u;
+                }
+                rp.put(32 * tf + l31, 2 * vg + hf,
+                       u32x4_t{pack_bf16x2(hv[0], hv[1]), pack_bf16x2(hv[2], hv[3]), pack_bf16x2(hv[4], hv[5]),
+                               pack_bf16x2(hv[6], hv[7])});
+            }
+        const int col = hc0 + 4 * rp.get8_piece();   // 8-byte pieces: 4 columns each
+        char* hbase = p.h + ((size_t)(rt.row0 + 128 * wm) * I + col) * 2;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const int row = rp.get8_row(j);
+            const u32x2_t v = rp.get8(j);
+            if (row < rows_w && col < I) store_wt8(hbase + (size_t)row * I * 2, v);
         }
     }
 }
 
 // ------------------------------------------------------------- GEMM2 task
 // o[row0.., ct*256 .. +256) = h_e W_down[e] for one row tile.
-template <int NW, class Hook>
+template <class Hook>
 __device__ __forceinline__ void gemm2_task(const FwdParams& p, const RowTile rt, int ct,
                                            char* smem, Hook after_mainloop) {
-    typedef Geom<NW> G;
     const int d = p.s.d, I = p.s.I;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    DirectRowLoader<false> al;
-    {
-        const int m = min(wave * 32 + (lane & 31), rt.rows - 1);
-        al.rp = p.h + ((size_t)(rt.row0 + m) * I + (lane >> 5) * 32) * 2;
-    }
-    typedef StridedLoader<G::NT, 32> BL;
-    BL bl;
-    bl.init();
     const int n0 = ct * BN;
-    {
-        const int c = min(n0 + BL::TG::chunk() * 8, d - 8);
-        bl.ld_bytes = (size_t)d * 2;
-        bl.bp = p.w_down + (((size_t)rt.expert * I + BL::TG::k0()) * d + c) * 2;
-    }
-    f32x16_t acc[8];
-    mma_mainloop_direct<NW>(al, bl, I / BK, smem, wave * 32 < rt.rows, acc);
-    after_mainloop();
-    const int col = n0 + (lane & 31) * 8;
-    if (col < d) {
+    const Lane ln;
+    FragAddr fa;
+    frag_addresses<true, false>(fa, lds_addr(smem), ln);
+    KcLoader lb;
+    KsLoader la;
+    lb.n = KcLoader::blocks_for(ln, rt.rows);
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int m = wave * 32 + frag_row(v, lane);
-            if (m < rt.rows)
-                store_stream16(p.o + ((size_t)(rt.row0 + m) * d + col) * 2, pack_row8(acc, v));
-        }
+    for (int i = 0; i < 4; ++i) {
+        const int m = min(KcGeom::row(ln, i), rt.rows - 1);
+        lb.p[i] = p.h + ((size_t)(rt.row0 + m) * I + KcGeom::chunk(ln, i) * 8) * 2;
+        const int c = min(n0 + KsGeom::chunk(ln, i) * 8, d - 8);
+        la.p[i] = p.w_down + (((size_t)rt.expert * I + KsGeom::krow(ln, i)) * d + c) * 2;
     }
+    la.step = (long long)BK * d * 2;
+    f32x16_t acc[4][2];
+    mma_tile<true, false>(lb, la, I / BK, rt.rows, smem, fa, acc);
+    after_mainloop();
+    char* obase = p.o + ((size_t)rt.row0 * d + n0) * 2;
+    store_subtile_bf16(acc, smem, rt.rows, d - n0, [&](int row, int col, u32x4_t v) {
+        store_stream16(obase + ((size_t)row * d + col) * 2, v);
+    });
 }
 
 // ------------------------------------------------------------- combine task
@@ -304,8 +325,7 @@ __device__ __forceinline__ void combine_task(const FwdParams& p, int block) {
 // when the lists are empty and the combine runs as a launch of its own (fwd_tail_kernel).
 // phase >= 0: only that phase's tasks (staged schedule; the waits are already
 // satisfied by stream order).
-template <int NW>
-__global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
+__global__ void __launch_bounds__(kMmaThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
 fwd_worker_kernel(FwdParams p, int phase) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     __shared__ int s_task;
@@ -340,13 +360,18 @@ fwd_worker_kernel(FwdParams p, int phase) {
             issued = true;
         };
         if (id >= 0) {
-            const Task task = p.tasks[id];
+            // the task is the same for every lane: keep its fields in scalar registers
+            Task task = p.tasks[id];
+            task.idx = rfl(task.idx);
+            task.code = rfl(task.code);
+            task.row0 = rfl(task.row0);
+            task.rows = rfl(task.rows);
             const int type = task_type(task), ct = task_ct(task);
             if (phase >= 0 && type != phase) {
                 // staged launch: another phase's task, nothing to do
             } else if (type == TASK_GEMM1) {
                 const RowTile rt = task_row_tile(task);
-                gemm1_task<NW>(p, rt, ct, smem, issue);
+                gemm1_task(p, rt, ct, smem, issue);
                 wait_stores();
                 __syncthreads();   // the write-through h stores of every wave have completed
                 if (threadIdx.x == 0) add_relaxed(p.flag1 + task.idx, 1);
@@ -355,7 +380,7 @@ fwd_worker_kernel(FwdParams p, int phase) {
                 __syncthreads();
                 if (s_ok) {
                     const RowTile rt = task_row_tile(task);
-                    gemm2_task<NW>(p, rt, ct, smem, issue);
+                    gemm2_task(p, rt, ct, smem, issue);
                 }
             }
         } else {
@@ -371,7 +396,7 @@ fwd_worker_kernel(FwdParams p, int phase) {
             if (threadIdx.x == 0)
                 s_ok = wait_ge(ctrl + CTRL_DONE, ctrl[CTRL_NWAIT], ctrl, p.spin_ticks, CTRL_TAIL_WAIT_TICKS);
             __syncthreads();
-            if (s_ok) combine_task<NW>(p, -1 - id);
+            if (s_ok) combine_task<8>(p, -1 - id);
         }
         issue();           // tasks without a main loop (tail, skipped, given up)
         __syncthreads();   // every thread has read s_task / s_ok of this round
@@ -425,60 +450,56 @@ FwdLayout fwd_layout(const moe_shape_t& s, bool with_ho) {
 size_t fwd_workspace_bytes(const moe_shape_t& s) { return fwd_layout(s, true).total; }
 size_t fwd_ctrl_bytes(const moe_shape_t& s) { return fwd_layout(s, false).total; }
 
-// Resident worker slots per device and tile height: the one piece of process-wide state,
-// filled on first use under a lock and constant afterwards.
+// Resident worker slots per device: the one piece of process-wide state, filled on first use
+// under a lock and constant afterwards.
 static std::mutex g_workers_mu;
-static int g_workers[kMaxDevices * 2];
+static int g_workers[kMaxDevices];
 
-template <int NW>
 static int resident_workers(int* out) {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return MOE_ERR_HIP;
-    const int slot = dev * 2 + (NW == 8 ? 1 : 0);
     std::lock_guard<std::mutex> lock(g_workers_mu);
-    if (g_workers[slot] == 0) {
-        if (hipFuncSetAttribute((const void*)fwd_worker_kernel<NW>,
-                                hipFuncAttributeMaxDynamicSharedMemorySize,
-                                Geom<NW>::SMEM) != hipSuccess)
+    if (g_workers[dev] == 0) {
+        if (hipFuncSetAttribute((const void*)fwd_worker_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                kMmaSmem) != hipSuccess)
             return MOE_ERR_HIP;
         int per_cu = 0, cus = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fwd_worker_kernel<NW>,
-                                                         Geom<NW>::NT, Geom<NW>::SMEM) != hipSuccess)
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fwd_worker_kernel, kMmaThreads,
+                                                         kMmaSmem) != hipSuccess)
             return MOE_ERR_HIP;
         if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
             return MOE_ERR_HIP;
         if (per_cu < 1 || cus < 1) return MOE_ERR_HIP;
-        g_workers[slot] = per_cu * cus;
+        g_workers[dev] = per_cu * cus;
     }
-    *out = g_workers[slot];
+    *out = g_workers[dev];
     return MOE_OK;
 }
 
-template <int NW>
-static int fwd_launch_nw(FwdParams& p, const moe_opts_t& opts, hipStream_t st) {
+// BM = rows per row tile: 256, or 128 (every tile then leaves the upper half of the workgroup's
+// rows empty; kept as an option because results must not depend on it).
+template <int BM>
+static int fwd_launch_bm(FwdParams& p, const moe_opts_t& opts, hipStream_t st) {
     int resident = 0;
-    int rc = resident_workers<NW>(&resident);
+    int rc = resident_workers(&resident);
     if (rc != MOE_OK) return rc;
     int workers = opts.workers > 0 ? min(opts.workers, resident) : resident;
     p.workers = workers;
-    hipLaunchKernelGGL(fwd_prologue_kernel<Geom<NW>::BM>, dim3(1), dim3(1024), 0, st, p);
+    hipLaunchKernelGGL(fwd_prologue_kernel<BM>, dim3(1), dim3(1024), 0, st, p);
     if (opts.schedule == 2) {
         for (int phase = 0; phase < 3; ++phase)
-            hipLaunchKernelGGL(fwd_worker_kernel<NW>, dim3(workers), dim3(Geom<NW>::NT),
-                               Geom<NW>::SMEM, st, p, phase);
+            hipLaunchKernelGGL(fwd_worker_kernel, dim3(workers), dim3(kMmaThreads), kMmaSmem, st, p, phase);
     } else if (opts.schedule != 1) {   // 0 (default) and 3: GEMM MegaKernel, then the tail tasks
-        hipLaunchKernelGGL(fwd_worker_kernel<NW>, dim3(workers), dim3(Geom<NW>::NT),
-                           Geom<NW>::SMEM, st, p, -2);
+        hipLaunchKernelGGL(fwd_worker_kernel, dim3(workers), dim3(kMmaThreads), kMmaSmem, st, p, -2);
         const int n_tail = (p.s.T + kCombineTokens - 1) / kCombineTokens;
         if (n_tail > 0 && !opts.skip_tail) {
             if (p.s.k <= 8)
-                hipLaunchKernelGGL((fwd_tail_kernel<NW, 8>), dim3(n_tail), dim3(Geom<NW>::NT), 0, st, p);
+                hipLaunchKernelGGL((fwd_tail_kernel<8, 8>), dim3(n_tail), dim3(kMmaThreads), 0, st, p);
             else
-                hipLaunchKernelGGL((fwd_tail_kernel<NW, kMaxTopK>), dim3(n_tail), dim3(Geom<NW>::NT), 0, st, p);
+                hipLaunchKernelGGL((fwd_tail_kernel<8, kMaxTopK>), dim3(n_tail), dim3(kMmaThreads), 0, st, p);
         }
     } else {
-        hipLaunchKernelGGL(fwd_worker_kernel<NW>, dim3(workers), dim3(Geom<NW>::NT),
-                           Geom<NW>::SMEM, st, p, -1);
+        hipLaunchKernelGGL(fwd_worker_kernel, dim3(workers), dim3(kMmaThreads), kMmaSmem, st, p, -1);
     }
     return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
@@ -509,7 +530,7 @@ int fwd_launch(const moe_shape_t& s, const void* x, const void* w_gate, const vo
     p.max_rt = L.max_rt;
     const int ms = opts.spin_limit_ms > 0 ? opts.spin_limit_ms : 2000;
     p.spin_ticks = (long long)ms * 100000ll;   // wall_clock64 ticks at 100 MHz
-    return nw == 4 ? fwd_launch_nw<4>(p, opts, st) : fwd_launch_nw<8>(p, opts, st);
+    return nw == 4 ? fwd_launch_bm<128>(p, opts, st) : fwd_launch_bm<256>(p, opts, st);
 }
 
 
