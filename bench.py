@@ -12,6 +12,9 @@ workload has a backward).  Prints ONE JSON line:
               events around the call without its tail kernel; roofline_forward carries the
               forward GEMM MegaKernel beside it
   cpu_baseline  the CPU oracle timed on a bounded sample of the same workload
+  measured_ceilings  what this GPU sustains on a matrix-instruction-only kernel and on a plain
+              copy, with the shader clock under that load, measured in this run; the
+              roofline fractions stay against the published peaks
 
 Usage: python bench.py [--gpus 1] [--steps K] [--warmup W] [--config N]
        python bench.py --model-shapes all [--tokens 8192] [--ep 8]   (sweep, one line per shape)
@@ -56,6 +59,8 @@ def parse():
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="also launch the plain copy kernel on this many MiB, 5 times "
                          "(scale for the HBM byte counters of a rocprofv3 --pmc run)")
+    ap.add_argument("--ceilings-only", action="store_true",
+                    help="print only the measured matrix-instruction / copy / clock ceilings (one JSON line)")
     return ap.parse_args()
 
 
@@ -89,6 +94,41 @@ def measured_traffic(cfg_name, kernel):
     return None
 
 
+def cpu_model():
+    try:
+        for line in Path("/proc/cpuinfo").read_text().splitlines():
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def measured_ceilings(moe):
+    """Sustained matrix-instruction and copy rates of this GPU, measured here: a kernel of
+    independent bf16 MFMA chains (no memory traffic) on every CU, and the library's copy kernel on
+    1 GiB.  The shader clock is the kernel's own cycle counter over its 100 MHz wall clock."""
+    import torch
+    props = torch.cuda.get_device_properties(0)
+    cus = props.multi_processor_count
+    for _ in range(2):   # the first run ramps the clock up
+        moe.moe_calibration_mfma(cus, 8, 20000)
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    r = moe.moe_calibration_mfma(cus, 8, 40000)
+    b.record()
+    torch.cuda.synchronize()
+    mfma_tflops = r["flop"] / (a.elapsed_time(b) * 1e-3) / 1e12
+    clock_mhz = 100.0 * r["shader_clocks"] / max(1, r["ticks_100mhz"])
+    src = torch.zeros(1 << 30, dtype=torch.uint8, device="cuda")
+    dst = torch.empty_like(src)
+    ms = event_ms(lambda: moe.moe_calibration_copy(dst, src), 10)
+    del src, dst
+    return {"mfma_bf16_tflops": mfma_tflops, "shader_clock_mhz_under_mfma_load": clock_mhz,
+            "copy_gbs_read_plus_write": 2.0 * (1 << 30) / (ms[1] * 1e-3) / 1e9,
+            "published": {"mfma_bf16_tflops": MFMA_BF16_PEAK_TFLOPS, "hbm_gbs": HBM_PEAK_GBS}}
+
+
 def cpu_baseline(cfg, inp, has_bwd, budget_s):
     """The oracle as it stands, on the rows of the first S local experts (same inputs)."""
     import numpy as np
@@ -118,7 +158,8 @@ def cpu_baseline(cfg, inp, has_bwd, budget_s):
     return {
         "value": flops / dt / 1e12,
         "unit": "TFLOP/s",
-        "cores": oracle.threads(),
+        "cores": oracle.threads(),   # omp_get_max_threads() of the oracle's library
+        "cpu_model": cpu_model(),
         "kind": "oracle",
         "sample": f"rows of the first {S} of {cfg.e_count} local experts ({rows} of the routed rows), "
                   f"route+forward{'+backward' if has_bwd else ''}, fp32 accumulate, {dt:.1f} s",
@@ -193,6 +234,13 @@ def main():
         assert torch.cuda.is_available(), "bench.py needs an MI355X"
         torch.cuda.set_device(0)
         sweep_model_shapes(args)
+        return
+    if args.ceilings_only:
+        import torch
+        import paper_2604_19241_amd as moe
+        assert torch.cuda.is_available(), "bench.py needs an MI355X"
+        torch.cuda.set_device(0)
+        print(json.dumps({"measured_ceilings": measured_ceilings(moe)}), flush=True)
         return
     import torch
     import moe_synth
@@ -285,8 +333,6 @@ def main():
     cold_bwd = event_ms(bwd, nc, before=flush) if has_bwd else None
     del flush_src, flush_dst
     fwd_tflops = f_fwd / (ms_fwd[0] * 1e-3) / 1e12
-    # waves per workgroup (tile height 32 * nw): 8 unless 128-row tiles are asked for
-    nw = 4 if args.tile_rows == 128 else 8
     # The GEMM MegaKernels alone: the same calls without their tail kernel (combine / dX).  With
     # the other schedules the tail runs inside the worker launches and the whole call is timed.
     split = args.schedule in (0, 3)
@@ -308,6 +354,8 @@ def main():
     if has_bwd:
         bwd()
 
+    ceilings = measured_ceilings(moe)
+
     def roof(kernel, what, flops, ms, ms_call):
         tf = flops / (ms[0] * 1e-3) / 1e12
         return {
@@ -319,14 +367,17 @@ def main():
             "unit": "TFLOP/s",
             "frac": tf / MFMA_BF16_PEAK_TFLOPS,
             "traffic": measured_traffic(cfg.name, kernel),
+            "traffic_source": f"profiles/hbm_traffic_{cfg.name.replace('-', '_')}.txt (committed summary of "
+                              f"rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command; not measured in this run)",
+            "frac_of_measured_mfma": tf / ceilings["mfma_bf16_tflops"],
             "flops_per_launch": flops,
             "avg_ms": ms[0], "median_ms": ms[1], "min_ms": ms[2],
             "tail_kernel_ms": (ms_call[0] - ms[0]) if split else None,
         }
 
-    roof_fwd = roof(f"fwd_worker_kernel<{nw}>", "forward GEMM MegaKernel, 6*A*d*I flop per launch",
+    roof_fwd = roof("fwd_worker_kernel", "forward GEMM MegaKernel, 6*A*d*I flop per launch",
                     f_fwd, ms_fwd_mega, ms_fwd)
-    roof_bwd = roof(f"bwd_worker_kernel<{nw}>", "backward GEMM MegaKernel, 12*A*d*I flop per launch",
+    roof_bwd = roof("bwd_worker_kernel", "backward GEMM MegaKernel, 12*A*d*I flop per launch",
                     f_bwd, ms_bwd_mega, ms_bwd) if has_bwd else None
     roofline = roof_bwd if has_bwd else roof_fwd
     counts = state["r"].counts.cpu().tolist()
@@ -359,6 +410,7 @@ def main():
         "backward_tflops": (f_bwd / (ms_bwd[0] * 1e-3) / 1e12) if ms_bwd else None,
         "expert_load": moe_synth.histogram_summary(counts),
         "roofline": roofline,
+        "measured_ceilings": ceilings,
     }
     if has_bwd:
         out["roofline_forward"] = roof_fwd

@@ -53,14 +53,10 @@ def _load(acc: str):
 
 
 def threads() -> int:
-    """OpenMP threads the oracle will use (OMP_NUM_THREADS, else all cores)."""
-    v = os.environ.get("OMP_NUM_THREADS")
-    if v:
-        try:
-            return max(1, int(v.split(",")[0]))
-        except ValueError:
-            pass
-    return os.cpu_count() or 1
+    """Threads the oracle's parallel loops run on: omp_get_max_threads() of the loaded library."""
+    fn = getattr(_load("f32"), "oracle_max_threads_f32")
+    fn.restype = ctypes.c_int
+    return max(1, int(fn()))
 
 
 def _shape_arr(shape: dict) -> np.ndarray:

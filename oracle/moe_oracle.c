@@ -40,6 +40,9 @@
  * finite differences, autograd).  The paper prints no worked numeric example
  * of y or of a gradient, so absolute values are pinned by those means only.
  */
+#ifdef _OPENMP
+#include <omp.h>
+#endif
 #include <math.h>
 #include <stdint.h>
 #include <stdlib.h>
@@ -645,4 +648,14 @@ int FN(oracle_route_backward)(const int32_t* sh, const float* logits, const int3
 /* The rounding rule on its own, so a test can pin it against a library cast. */
 void FN(oracle_round_bf16)(const double* in, double* out, int64_t n) {
     for (int64_t i = 0; i < n; ++i) out[i] = (double)round_to_bf16((acc_t)in[i]);
+}
+
+/* Threads the parallel loops above run on (what omp_get_max_threads() reports in this
+ * process): a benchmark that times the oracle states it beside the timing. */
+int FN(oracle_max_threads)(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
 }

@@ -55,6 +55,29 @@ def counter_avgs(con):
     return out
 
 
+def counter_avgs_by_cycle(con, cycles):
+    """{kernel: {phase: {counter: (avg, dispatches)}}} for the kernels named in `cycles`
+    ({short kernel name: launches per pass}): the i-th dispatch of such a kernel, in dispatch
+    order, is launch i % cycle of a pass (a staged schedule launches the worker kernel once per
+    phase, always in the same order)."""
+    q = ("select kernel_name, dispatch_id, counter_name, value from counters_collection "
+         "order by dispatch_id")
+    seen, acc = {}, {}
+    for k, disp, c, v in con.execute(q):
+        name = _short(k)
+        if name not in cycles:
+            continue
+        order = seen.setdefault(name, {})
+        if disp not in order:
+            order[disp] = len(order)
+        ph = order[disp] % cycles[name]
+        tot = acc.setdefault(name, {}).setdefault(ph, {}).setdefault(c, [0.0, 0])
+        tot[0] += v
+        tot[1] += 1
+    return {k: {ph: {c: (t[0] / t[1], t[1]) for c, t in d.items()} for ph, d in phs.items()}
+            for k, phs in acc.items()}
+
+
 def _header(f, cmds):
     f.write("commands (MI355X box, from the repo root after `cd /tmp; export TMPDIR=/tmp` "
             "and cd back):\n")
@@ -65,11 +88,13 @@ def _header(f, cmds):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("mode", choices=["kernels", "counters", "traffic"])
+    ap.add_argument("mode", choices=["kernels", "counters", "traffic", "phases"])
     ap.add_argument("paths", nargs="+")
     ap.add_argument("--cmd", action="append", default=[])
     ap.add_argument("--copy-bytes", type=int, default=0)
     ap.add_argument("--note", action="append", default=[])
+    ap.add_argument("--cycle", action="append", default=[],
+                    help="phases mode: kernel=launches per pass, e.g. fwd_worker_kernel=3")
     a = ap.parse_args()
     out = a.paths[-1]
     with open(out, "w") as f:
@@ -82,6 +107,13 @@ def main():
             f.write("%-64s %6s %12s %12s %7s\n" % ("kernel", "calls", "total_us", "avg_us", "pct"))
             for n, calls, tot, avg, pct in kernel_rows(_db(a.paths[0])):
                 f.write("%-64s %6d %12.1f %12.3f %7.2f\n" % (_short(n), calls, tot, avg, pct))
+        elif a.mode == "phases":
+            cycles = {c.split("=")[0]: int(c.split("=")[1]) for c in a.cycle}
+            for k, phs in sorted(counter_avgs_by_cycle(_db(a.paths[0]), cycles).items()):
+                for ph, d in sorted(phs.items()):
+                    f.write(f"{k} launch {ph} of {cycles[k]}\n")
+                    for n, (v, c) in sorted(d.items()):
+                        f.write("   %-34s avg/dispatch=%.6g  (dispatches=%d)\n" % (n, v, c))
         elif a.mode == "counters":
             for k, d in sorted(counter_avgs(_db(a.paths[0])).items()):
                 f.write(_short(k) + "\n")
