@@ -46,6 +46,9 @@ def parse():
     ap.add_argument("--schedule", type=int, default=0)
     ap.add_argument("--tile-rows", type=int, default=0)
     ap.add_argument("--workers", type=int, default=0)
+    ap.add_argument("--dw-split-rows", type=int, default=0,
+                    help="backward: cut the weight-gradient reduction of experts with more rows than this "
+                         "at fixed points (moe_opts_t.dw_split_rows); 0 = one sum per element")
     ap.add_argument("--no-backward", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
@@ -255,10 +258,12 @@ def main():
 
     inp = moe_synth.make_inputs(cfg, with_dy=has_bwd)
     dev = {k: v.cuda() for k, v in inp.items()}
-    opts = moe.make_opts(schedule=args.schedule, tile_rows=args.tile_rows, workers=args.workers)
+    opts = moe.make_opts(schedule=args.schedule, tile_rows=args.tile_rows, workers=args.workers,
+                         dw_split_rows=args.dw_split_rows)
     ws_route = torch.empty(sizes["route"], dtype=torch.uint8, device="cuda")
     ws_fwd = torch.empty(sizes["fwd"], dtype=torch.uint8, device="cuda")
-    ws_bwd = torch.empty(sizes["bwd"], dtype=torch.uint8, device="cuda") if has_bwd else None
+    ws_bwd = (torch.empty(moe.moe_backward_workspace_bytes(shape, opts), dtype=torch.uint8, device="cuda")
+              if has_bwd else None)
     saved = moe.alloc_saved(shape, "cuda") if has_bwd else None
     y = torch.empty((cfg.T, cfg.d), dtype=torch.bfloat16, device="cuda")
     state = {}
@@ -337,7 +342,7 @@ def main():
     # the other schedules the tail runs inside the worker launches and the whole call is timed.
     split = args.schedule in (0, 3)
     opts_mega = moe.make_opts(schedule=args.schedule, tile_rows=args.tile_rows, workers=args.workers,
-                              skip_tail=1 if split else 0)
+                              skip_tail=1 if split else 0, dw_split_rows=args.dw_split_rows)
 
     def fwd_mega():
         moe.moe_fused_forward(shape, dev["x"], dev["w_gate"], dev["w_up"], dev["w_down"],
@@ -397,7 +402,8 @@ def main():
         "config": {"workload": f"configs[{args.config}] {cfg.name}: T={cfg.T} d={cfg.d} E={cfg.E} "
                                f"k={cfg.k} I={cfg.I} local_experts={cfg.e_count}, route+forward"
                                f"{'+backward' if has_bwd else ''}",
-                   "routed_rows": A, "schedule": args.schedule, "tile_rows": args.tile_rows},
+                   "routed_rows": A, "schedule": args.schedule, "tile_rows": args.tile_rows,
+                   "dw_split_rows": args.dw_split_rows},
         "tokens_per_s": cfg.T / (ms_per_step * 1e-3),
         "pct_of_bf16_mfma_peak": 100.0 * value / MFMA_BF16_PEAK_TFLOPS,
         "phases_ms": {"route": ms_route[0], "forward": ms_fwd[0],

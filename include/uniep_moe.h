@@ -111,13 +111,30 @@ typedef struct {
                               of a mixed-precision training loop.  Experts without rows are left
                               untouched.  Every element is updated by exactly one tile, so the
                               result is as reproducible as with 0. */
-    int32_t reserved[2];   /* must be 0 */
+    int32_t dw_split_rows; /* moe_fused_backward only.  0 = every weight-gradient element is one sum over
+                              the expert's rows in ascending order.  S > 0 (a multiple of 64, at least
+                              256): the reduction of an expert with more than S rows is cut at the fixed
+                              points S, 2S, ... (a function of the expert's row count only) into parts
+                              that run as tasks of their own; the fp32 partial tiles are added in the
+                              order of the parts.  More parallelism for a few very large experts
+                              (skewed routing), at the price Section 6.3 discusses: the result is still
+                              bitwise identical from run to run, across schedules and worker counts, but
+                              not to the S = 0 result (another association of the same sum).  Needs the
+                              larger workspace that moe_backward_workspace_bytes reports. */
+    int32_t reserved[1];   /* must be 0 */
 } moe_opts_t;
 
 /* Bytes each call needs (host outputs; any may be NULL).  `saved_bytes` is the
  * size of the optional activation stash forward fills for backward. */
 int moe_workspace_bytes(const moe_shape_t* shape, size_t* route_ws, size_t* fwd_ws,
                         size_t* bwd_ws, size_t* saved_bytes);
+
+/* Workspace bytes of moe_fused_backward with these options (host output).  Equal to bwd_ws of
+ * moe_workspace_bytes unless opts->dw_split_rows > 0: the partial tiles of the split
+ * weight-gradient reductions (Section 6.3, the cost of a fixed reduction order) are sized for
+ * the worst routing, 2 * T * k / dw_split_rows parts of every output tile of an expert.
+ * MOE_ERR_ARG for options moe_fused_backward would reject. */
+int moe_backward_workspace_bytes(const moe_shape_t* shape, const moe_opts_t* opts, size_t* bwd_ws);
 
 /* Byte offsets inside the `saved` stash (host outputs), for a given shape:
  *   gu  [A_cap, 2*I] bf16  per row: G (I values) then U (I values), A_cap = T*k

@@ -19,7 +19,7 @@ LIB_PATH = _PKG / "libuniep_moe.so"
 MOE_OK = 0
 MOE_ERR_ARG, MOE_ERR_SHAPE, MOE_ERR_WORKSPACE, MOE_ERR_HIP, MOE_ERR_DEVICE = -1, -2, -3, -4, -5
 
-EXPORTS = ("moe_workspace_bytes", "moe_saved_layout", "moe_route", "moe_fused_forward",
+EXPORTS = ("moe_workspace_bytes", "moe_backward_workspace_bytes", "moe_saved_layout", "moe_route", "moe_fused_forward",
            "moe_fused_backward", "moe_route_backward", "moe_global_map", "moe_device_status",
            "moe_status_string", "moe_calibration_copy", "moe_perf_model_eval",
            "moe_perf_model_search", "moe_route_static", "moe_calibration_mfma")
@@ -40,7 +40,8 @@ class MoEOpts(ctypes.Structure):
     _fields_ = [("schedule", ctypes.c_int32), ("workers", ctypes.c_int32),
                 ("spin_limit_ms", ctypes.c_int32), ("tile_rows", ctypes.c_int32),
                 ("skip_tail", ctypes.c_int32), ("dw_accumulate", ctypes.c_int32),
-                ("reserved", ctypes.c_int32 * 2)]
+                ("dw_split_rows", ctypes.c_int32),
+                ("reserved", ctypes.c_int32 * 1)]
 
 
 class MoEError(RuntimeError):
@@ -84,11 +85,12 @@ def make_shape(T, d, E, k, I, e_start=0, e_count=None) -> MoEShape:
 
 
 def make_opts(schedule=0, workers=0, spin_limit_ms=0, tile_rows=0, skip_tail=0,
-              dw_accumulate=0) -> MoEOpts:
+              dw_accumulate=0, dw_split_rows=0) -> MoEOpts:
     o = MoEOpts()
     o.schedule, o.workers, o.spin_limit_ms, o.tile_rows = schedule, workers, spin_limit_ms, tile_rows
     o.skip_tail = skip_tail
     o.dw_accumulate = dw_accumulate
+    o.dw_split_rows = dw_split_rows
     return o
 
 
@@ -105,6 +107,14 @@ def moe_workspace_bytes(shape: MoEShape) -> dict:
     _check(load_library().moe_workspace_bytes(ctypes.byref(shape), *[ctypes.byref(v) for v in vals]),
            "moe_workspace_bytes")
     return dict(zip(("route", "fwd", "bwd", "saved"), (int(v.value) for v in vals)))
+
+
+def moe_backward_workspace_bytes(shape: MoEShape, opts: MoEOpts | None = None) -> int:
+    v = ctypes.c_size_t(0)
+    _check(load_library().moe_backward_workspace_bytes(
+        ctypes.byref(shape), ctypes.byref(opts) if opts is not None else None, ctypes.byref(v)),
+        "moe_backward_workspace_bytes")
+    return int(v.value)
 
 
 def moe_saved_layout(shape: MoEShape) -> dict:
@@ -236,7 +246,7 @@ def moe_fused_backward(shape: MoEShape, dy, x, w_gate, w_up, w_down, routing: Ro
             if want_dtopk_w else None,
         }
     if ws is None:
-        ws = _ws(moe_workspace_bytes(shape)["bwd"], dev)
+        ws = _ws(moe_backward_workspace_bytes(shape, opts), dev)
     cs = routing.c_struct()
     _check(load_library().moe_fused_backward(
         ctypes.byref(shape), _ptr(dy), _ptr(x), _ptr(w_gate), _ptr(w_up), _ptr(w_down),

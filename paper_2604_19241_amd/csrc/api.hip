@@ -19,7 +19,8 @@ size_t fwd_ctrl_bytes(const moe_shape_t& s);
 int fwd_launch(const moe_shape_t& s, const void* x, const void* w_gate, const void* w_up,
                const void* w_down, const moe_routing_t& r, void* y, char* gu, char* h, char* o,
                char* ws, const moe_opts_t& opts, int nw, hipStream_t st);
-size_t bwd_workspace_bytes(const moe_shape_t& s);
+size_t bwd_workspace_bytes(const moe_shape_t& s, int split_rows);
+bool bwd_split_ok(const moe_shape_t& s, int split_rows);
 int bwd_launch(const moe_shape_t& s, const void* dy, const void* x, const void* w_gate,
                const void* w_up, const void* w_down, const moe_routing_t& r, const char* gu,
                const char* h, const char* o, void* dx, void* dw_gate, void* dw_up, void* dw_down,
@@ -59,8 +60,9 @@ int check_opts(const moe_opts_t* o, moe_opts_t* out) {
     if (d.tile_rows != 0 && d.tile_rows != 128 && d.tile_rows != 256) return MOE_ERR_ARG;
     if (d.skip_tail != 0 && d.skip_tail != 1) return MOE_ERR_ARG;
     if (d.dw_accumulate != 0 && d.dw_accumulate != 1) return MOE_ERR_ARG;
-    for (int i = 0; i < 2; ++i)
-        if (d.reserved[i] != 0) return MOE_ERR_ARG;
+    if (d.dw_split_rows < 0 || d.dw_split_rows % 64 != 0 || (d.dw_split_rows != 0 && d.dw_split_rows < 256))
+        return MOE_ERR_ARG;
+    if (d.reserved[0] != 0) return MOE_ERR_ARG;
     *out = d;
     return MOE_OK;
 }
@@ -162,8 +164,19 @@ int moe_workspace_bytes(const moe_shape_t* shape, size_t* route_ws, size_t* fwd_
     if (rc != MOE_OK) return rc;
     if (route_ws) *route_ws = route_workspace_bytes(*shape);
     if (fwd_ws) *fwd_ws = fwd_workspace_bytes(*shape);
-    if (bwd_ws) *bwd_ws = bwd_workspace_bytes(*shape);
+    if (bwd_ws) *bwd_ws = bwd_workspace_bytes(*shape, 0);
     if (saved_bytes) *saved_bytes = saved_layout(*shape).total;
+    return MOE_OK;
+}
+
+int moe_backward_workspace_bytes(const moe_shape_t* shape, const moe_opts_t* opts, size_t* bwd_ws) {
+    int rc = check_shape(shape);
+    if (rc != MOE_OK) return rc;
+    moe_opts_t o;
+    rc = check_opts(opts, &o);
+    if (rc != MOE_OK) return rc;
+    if (!bwd_ws || !bwd_split_ok(*shape, o.dw_split_rows)) return MOE_ERR_ARG;
+    *bwd_ws = bwd_workspace_bytes(*shape, o.dw_split_rows);
     return MOE_OK;
 }
 
@@ -257,7 +270,8 @@ int moe_fused_backward(const moe_shape_t* shape, const void* dy, const void* x, 
         !aligned(dw_up, 16) || !aligned(dw_down, 16) || !aligned(ws, 256) ||
         !aligned(saved, 256) || !aligned(dtopk_w, 4))
         return MOE_ERR_ARG;
-    if (ws_bytes < bwd_workspace_bytes(*shape)) return MOE_ERR_WORKSPACE;
+    if (!bwd_split_ok(*shape, o.dw_split_rows)) return MOE_ERR_ARG;
+    if (ws_bytes < bwd_workspace_bytes(*shape, o.dw_split_rows)) return MOE_ERR_WORKSPACE;
     const SavedLayout L = saved_layout(*shape);
     const char* sv = (const char*)saved;
     return bwd_launch(*shape, dy, x, w_gate, w_up, w_down, *routing, sv + L.gu, sv + L.h, sv + L.o,

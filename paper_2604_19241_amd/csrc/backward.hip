@@ -19,6 +19,7 @@
 //   4  dX[t] = sum_j dXp[row(t,j)] in slot order; dtopk_w = <dY[t], o[row]>
 #include "mma.hpp"
 
+#include <algorithm>
 #include <mutex>
 
 namespace uniep {
@@ -58,11 +59,24 @@ struct BwdParams {
     int nct_dh, nct_dxp;        // column tiles of phase 0 (256 of I) and phase 2 (256 of d)
     int mt_dwd, nt_dwd;         // dW_down tiles per expert: ceil(I/256) x ceil(d/256)
     int mt_dwgu, nt_dwgu;       // dW_gate/up tiles per expert: ceil(d/256) x ceil(I/128)
+    int split_rows;             // 0, or the fixed split distance of the weight-gradient reductions (multiple of 64)
+    int32_t* split_base;        // [e_count]  first partial-tile slot of expert e (split experts only)
+    int32_t* split_cnt;         // [split tiles]  partial tiles written so far, per output tile of a split expert
+    int32_t* split_tile0;       // [e_count]  first entry of expert e in split_cnt
+    char* split_buf;            // [slots][256 KB]  fp32 partial tiles in accumulator layout
     int n_dots;                 // partial sums per routed row: 4 * nct_dh
     int bm;                     // rows per row tile (256, or 128)
     int workers;                // workgroups of the worker launch (the tail waits for all of them)
     long long spin_ticks;
 };
+
+// Weight-gradient tasks carry (output row tile, part, parts) in Task.idx.
+__host__ __device__ __forceinline__ int wgrad_idx(int mt, int part, int parts) { return mt | (part << 8) | (parts << 20); }
+__device__ __forceinline__ int wgrad_mt(int idx) { return idx & 0xff; }
+__device__ __forceinline__ int wgrad_part(int idx) { return (idx >> 8) & 0xfff; }
+__device__ __forceinline__ int wgrad_parts(int idx) { return (idx >> 20) & 0xfff; }
+constexpr int kMaxSplitParts = 0xfff;
+constexpr size_t kPartialTileBytes = (size_t)BMAX * BN * sizeof(float);
 
 // ------------------------------------------------------------- row metadata
 // row_tok[r] = token of expert row r, row_w[r] = its gate (the backward
@@ -103,10 +117,17 @@ __global__ void __launch_bounds__(1024) bwd_prologue_kernel(BwdParams p) {
         cnt = p.offsets[e + 1] - p.offsets[e];
         nt = (cnt + BM - 1) / BM;
     }
+    // Section 6.3 prices bitwise reproducibility in the backward pass: the order of the
+    // weight-gradient reduction is fixed.  An expert with more than split_rows rows has that
+    // reduction cut at the fixed points r0 + j * split_rows (a function of the counts only) into
+    // `parts` tasks per output tile; their fp32 partial tiles are added in the order of j.
+    const int parts = (p.split_rows > 0 && cnt > p.split_rows) ? (cnt + p.split_rows - 1) / p.split_rows : 1;
+    __shared__ int32_t s_parts[kMaxExperts];
+    s_parts[e] = parts;
     s_plan.cost[e] = cnt;
     s_scan[e] = nt;
     s_ga[e] = (e < ec) ? nt * p.nct_dh : 0;
-    s_gb[e] = (e < ec) ? nt * p.nct_dxp + per_dwgu + per_dwd : 0;
+    s_gb[e] = (e < ec) ? nt * p.nct_dxp + (per_dwgu + per_dwd) * parts : 0;
     __syncthreads();
     for (int off = 1; off < kMaxExperts; off <<= 1) {
         const int32_t add = (e >= off) ? s_scan[e - off] : 0;
@@ -115,6 +136,26 @@ __global__ void __launch_bounds__(1024) bwd_prologue_kernel(BwdParams p) {
         __syncthreads();
     }
     const int nrt = s_scan[kMaxExperts - 1];
+    if (p.split_rows > 0) {   // slots of the split experts: output tiles, and partial tiles
+        __shared__ int32_t s_st[kMaxExperts];
+        __shared__ int32_t s_sp[kMaxExperts];
+        const int tiles = (e < ec && parts > 1) ? per_dwgu + per_dwd : 0;
+        s_st[e] = tiles;
+        s_sp[e] = tiles * parts;
+        __syncthreads();
+        for (int off = 1; off < kMaxExperts; off <<= 1) {
+            const int32_t a0 = (e >= off) ? s_st[e - off] : 0, a1 = (e >= off) ? s_sp[e - off] : 0;
+            __syncthreads();
+            s_st[e] += a0;
+            s_sp[e] += a1;
+            __syncthreads();
+        }
+        if (e < ec) {
+            p.split_tile0[e] = s_st[e] - tiles;
+            p.split_base[e] = s_sp[e] - tiles * parts;
+            for (int i = 0; i < tiles; ++i) p.split_cnt[s_st[e] - tiles + i] = 0;
+        }
+    }
     plan_lists(s_plan, ec);
     if (e < kQueues) {   // length of list e
         int len = 0;
@@ -149,7 +190,8 @@ __global__ void __launch_bounds__(1024) bwd_prologue_kernel(BwdParams p) {
     __syncthreads();
     for (int x = e >> 6; x < ec; x += 16) {   // one wave writes the two blocks of an expert
         const int rt0 = s_rt0[x], lane = e & 63;
-        const int n_dxp = s_gb[x] - per_dwgu - per_dwd;
+        const int parts_x = s_parts[x];
+        const int n_dxp = s_gb[x] - (per_dwgu + per_dwd) * parts_x;
         Task* ta = p.tasks + s_ta[x];
         Task* tb = p.tasks + s_tb[x];
         const int r0 = s_r0[x], rows_x = s_plan.cost[x];
@@ -164,11 +206,22 @@ __global__ void __launch_bounds__(1024) bwd_prologue_kernel(BwdParams p) {
             tb[block_pos<true>(j, ct, nt_x, p.nct_dxp)] =
                 Task{rt0 + j, task_code(B_DXP, x, ct), r0 + j * BM, min(BM, rows_x - j * BM)};
         });
+        // weight-gradient tasks: idx = output row tile | part << 8 | parts << 20; row0 / rows = the part's rows
         for_each_tile(lane, p.mt_dwgu, p.nt_dwgu, [&](int mt, int nt) {
-            tb[n_dxp + block_pos<false>(mt, nt, p.mt_dwgu, p.nt_dwgu)] = Task{mt, task_code(B_DWGU, x, nt), r0, rows_x};
+            for (int j = 0; j < parts_x; ++j) {
+                const int first = (parts_x > 1) ? j * p.split_rows : 0;
+                const int len = (parts_x > 1) ? min(p.split_rows, rows_x - first) : rows_x;
+                tb[n_dxp + block_pos<false>(mt, nt, p.mt_dwgu, p.nt_dwgu) * parts_x + j] =
+                    Task{wgrad_idx(mt, j, parts_x), task_code(B_DWGU, x, nt), r0 + first, len};
+            }
         });
         for_each_tile(lane, p.mt_dwd, p.nt_dwd, [&](int mt, int nt) {
-            tb[n_dxp + per_dwgu + block_pos<false>(mt, nt, p.mt_dwd, p.nt_dwd)] = Task{mt, task_code(B_DWD, x, nt), r0, rows_x};
+            for (int j = 0; j < parts_x; ++j) {
+                const int first = (parts_x > 1) ? j * p.split_rows : 0;
+                const int len = (parts_x > 1) ? min(p.split_rows, rows_x - first) : rows_x;
+                tb[n_dxp + per_dwgu * parts_x + block_pos<false>(mt, nt, p.mt_dwd, p.nt_dwd) * parts_x + j] =
+                    Task{wgrad_idx(mt, j, parts_x), task_code(B_DWD, x, nt), r0 + first, len};
+            }
         });
     }
     if (e < CTRL_WORDS) {
@@ -325,12 +378,71 @@ __device__ __forceinline__ void accumulate8(float* q, const f32x16_t& a, int vg)
     __builtin_nontemporal_store(hi, (f32x4_t*)q + 1);
 }
 
+// ------------------------------------------------------------- split weight-gradient reductions
+// One part of a split reduction ends here: the fp32 accumulators go to the part's slot in
+// accumulator layout (every store instruction writes 1 KB of consecutive bytes), the tile's
+// counter is advanced, and the workgroup that finds all other parts already counted adds the
+// `parts` partial tiles in the order of the part index, starting from zero: the sum does not
+// depend on which workgroup adds, nor on the order in which the parts were computed.
+// Returns whether acc now holds the complete sum (the caller then stores the tile).
+__device__ __forceinline__ bool finish_part(const BwdParams& p, int e, int tile, int part, int parts,
+                                            f32x16_t (&acc)[4][2], int* s_flag) {
+    if (parts <= 1) return true;
+    typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+    const Lane ln;
+    const size_t lane_off = (size_t)ln.w * 32768 + (size_t)ln.l * 16;
+    char* slots = p.split_buf + ((size_t)p.split_base[e] + (size_t)tile * parts) * kPartialTileBytes;
+    char* mine = slots + (size_t)part * kPartialTileBytes + lane_off;
+#pragma unroll
+    for (int tf = 0; tf < 4; ++tf)
+#pragma unroll
+        for (int af = 0; af < 2; ++af)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const f32x4_t v = {acc[tf][af][4 * q], acc[tf][af][4 * q + 1], acc[tf][af][4 * q + 2], acc[tf][af][4 * q + 3]};
+                store_wt16(mine + ((tf * 2 + af) * 4 + q) * 1024, __builtin_bit_cast(u32x4_t, v));
+            }
+    wait_stores();
+    __syncthreads();   // the partial tile of every wave has reached memory
+    if (threadIdx.x == 0) {
+        const int before = __hip_atomic_fetch_add(p.split_cnt + p.split_tile0[e] + tile, 1, __ATOMIC_RELAXED,
+                                                  __HIP_MEMORY_SCOPE_AGENT);
+        if (before == parts - 1) fence_acquire();
+        *s_flag = before;
+    }
+    __syncthreads();
+    if (*s_flag != parts - 1) return false;
+#pragma unroll
+    for (int tf = 0; tf < 4; ++tf)
+#pragma unroll
+        for (int af = 0; af < 2; ++af)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[tf][af][v] = 0.f;
+    for (int j = 0; j < parts; ++j) {
+        const char* src = slots + (size_t)j * kPartialTileBytes + lane_off;
+#pragma unroll
+        for (int tf = 0; tf < 4; ++tf)
+#pragma unroll
+            for (int af = 0; af < 2; ++af)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const f32x4_t v = *(const f32x4_t*)(src + ((tf * 2 + af) * 4 + q) * 1024);
+                    acc[tf][af][4 * q] += v[0];
+                    acc[tf][af][4 * q + 1] += v[1];
+                    acc[tf][af][4 * q + 2] += v[2];
+                    acc[tf][af][4 * q + 3] += v[3];
+                }
+    }
+    return true;
+}
+
 // ------------------------------------------------------------- phase 1: dW_down
 // dW_down[e][i][c] = sum over the expert's rows r (ascending) of (gate_r h[r][i]) * dY[tok_r][c].
 // Output tile: 256 rows of I by 256 columns of d; both operands have k = r as their memory row.
 template <bool ACC, class Hook>
-__device__ __forceinline__ void dwd_task(const BwdParams& p, int e, int mt, int nt, int r0, int cnt,
-                                         char* smem, Hook after_mainloop) {
+__device__ __forceinline__ void dwd_task(const BwdParams& p, int e, int idx, int nt, int r0, int cnt,
+                                         char* smem, int* s_flag, Hook after_mainloop) {
+    const int mt = wgrad_mt(idx);
     const int d = p.s.d, I = p.s.I;
     const int m0 = mt * BMAX, n0 = nt * BN;
     const Lane ln;
@@ -350,6 +462,7 @@ __device__ __forceinline__ void dwd_task(const BwdParams& p, int e, int mt, int 
     f32x16_t acc[4][2];
     mma_tile<true, true>(lb, la, (cnt + BK - 1) / BK, min(BMAX, I - m0), smem, fa, acc);
     after_mainloop();
+    if (!finish_part(p, e, p.mt_dwgu * p.nt_dwgu + mt * p.nt_dwd + nt, wgrad_part(idx), wgrad_parts(idx), acc, s_flag)) return;
     if (ACC) {
         const Lane le;
 #pragma unroll
@@ -378,8 +491,9 @@ __device__ __forceinline__ void dwd_task(const BwdParams& p, int e, int mt, int 
 // Output tile: 256 rows of d by 128 columns of I, for both matrices at once: column fragment 0
 // of a wave holds dG columns, fragment 1 the same dU columns.
 template <bool ACC, class Hook>
-__device__ __forceinline__ void dwgu_task(const BwdParams& p, int e, int mt, int nt, int r0, int cnt,
-                                          char* smem, Hook after_mainloop) {
+__device__ __forceinline__ void dwgu_task(const BwdParams& p, int e, int idx, int nt, int r0, int cnt,
+                                          char* smem, int* s_flag, Hook after_mainloop) {
+    const int mt = wgrad_mt(idx);
     const int d = p.s.d, I = p.s.I;
     const int m0 = mt * BMAX, n0i = nt * (BN / 2);
     const Lane ln;
@@ -401,6 +515,7 @@ __device__ __forceinline__ void dwgu_task(const BwdParams& p, int e, int mt, int
     f32x16_t acc[4][2];
     mma_tile<true, true>(lb, la, (cnt + BK - 1) / BK, min(BMAX, d - m0), smem, fa, acc);
     after_mainloop();
+    if (!finish_part(p, e, mt * p.nt_dwgu + nt, wgrad_part(idx), wgrad_parts(idx), acc, s_flag)) return;
     if (ACC) {
         const Lane le;
 #pragma unroll
@@ -556,12 +671,13 @@ __device__ __forceinline__ void bwd_worker_body(const BwdParams& p, int phase, c
                 // weight-gradient tiles read what ALL dH tiles of the expert wrote (dG|dU, gate * h):
                 // its row tiles times the dH column tiles
                 const int e = task_expert(task);
-                const int need = (task.rows + p.bm - 1) / p.bm * p.nct_dh;
+                const int rows_e = p.offsets[e + 1] - p.offsets[e];   // (task.rows is the part's share)
+                const int need = (rows_e + p.bm - 1) / p.bm * p.nct_dh;
                 if (threadIdx.x == 0) s_ok = wait_ge(p.flag_e + e, need, ctrl, p.spin_ticks);
                 __syncthreads();
                 if (s_ok) {
-                    if (type == B_DWD) dwd_task<ACC>(p, e, task.idx, ct, task.row0, task.rows, smem, issue);
-                    else dwgu_task<ACC>(p, e, task.idx, ct, task.row0, task.rows, smem, issue);
+                    if (type == B_DWD) dwd_task<ACC>(p, e, task.idx, ct, task.row0, task.rows, smem, &s_ok, issue);
+                    else dwgu_task<ACC>(p, e, task.idx, ct, task.row0, task.rows, smem, &s_ok, issue);
                 }
             }
         } else {
@@ -616,11 +732,11 @@ __global__ void __launch_bounds__(64 * NW) bwd_tail_kernel(BwdParams p) {
 // ------------------------------------------------------------------ host side
 
 struct BwdLayout {
-    size_t ctrl, flag_rt, flag_e, tasks, row_tok, row_w, dgu, dxp, hw, dots, total;
+    size_t ctrl, flag_rt, flag_e, tasks, row_tok, row_w, dgu, dxp, hw, dots, split_base, split_tile0, split_cnt, split_buf, total;
     int max_rt, nct_dh, nct_dxp, mt_dwd, nt_dwd, mt_dwgu, nt_dwgu;
 };
 
-static BwdLayout bwd_layout(const moe_shape_t& s) {
+static BwdLayout bwd_layout(const moe_shape_t& s, int split_rows) {
     BwdLayout L;
     const size_t A_cap = (size_t)s.T * s.k;
     L.max_rt = (int)((A_cap + 127) / 128) + s.e_count;   // 128-row tiles need the most entries
@@ -630,8 +746,13 @@ static BwdLayout bwd_layout(const moe_shape_t& s) {
     L.nt_dwd = (s.d + BN - 1) / BN;
     L.mt_dwgu = (s.d + BMAX - 1) / BMAX;
     L.nt_dwgu = (s.I + BN / 2 - 1) / (BN / 2);
+    // split reductions: at most A_cap / split_rows experts have more than split_rows rows, and their
+    // parts number at most A_cap / split_rows more than that
+    const size_t tiles_pe = (size_t)L.mt_dwd * L.nt_dwd + (size_t)L.mt_dwgu * L.nt_dwgu;
+    const size_t split_experts = split_rows > 0 ? std::min(A_cap / split_rows, (size_t)s.e_count) : 0;
+    const size_t split_parts = split_rows > 0 ? A_cap / split_rows + split_experts : 0;
     const size_t max_tasks = (size_t)L.max_rt * (L.nct_dh + L.nct_dxp) +
-                             (size_t)s.e_count * (L.mt_dwd * L.nt_dwd + L.mt_dwgu * L.nt_dwgu) +
+                             (size_t)s.e_count * tiles_pe + split_parts * tiles_pe +
                              (s.T + kDxTokens - 1) / kDxTokens;
     size_t off = 0;
     L.ctrl = off;    off = align_up(off + CTRL_WORDS * sizeof(int), 256);
@@ -644,11 +765,21 @@ static BwdLayout bwd_layout(const moe_shape_t& s) {
     L.dxp = off;     off = align_up(off + A_cap * s.d * 2, 256);
     L.hw = off;      off = align_up(off + A_cap * s.I * 2, 256);
     L.dots = off;    off = align_up(off + (size_t)4 * L.nct_dh * A_cap * sizeof(float), 256);
+    L.split_base = off;  off = align_up(off + (size_t)s.e_count * sizeof(int32_t), 256);
+    L.split_tile0 = off; off = align_up(off + (size_t)s.e_count * sizeof(int32_t), 256);
+    L.split_cnt = off;   off = align_up(off + split_experts * tiles_pe * sizeof(int32_t), 256);
+    L.split_buf = off;   off = align_up(off + split_parts * tiles_pe * kPartialTileBytes, 256);
     L.total = off;
     return L;
 }
 
-size_t bwd_workspace_bytes(const moe_shape_t& s) { return bwd_layout(s).total; }
+size_t bwd_workspace_bytes(const moe_shape_t& s, int split_rows) { return bwd_layout(s, split_rows).total; }
+// parts per expert and output row tiles per expert must fit the fields of a weight-gradient task
+bool bwd_split_ok(const moe_shape_t& s, int split_rows) {
+    if (split_rows == 0) return true;
+    const BwdLayout L = bwd_layout(s, split_rows);
+    return (size_t)s.T * s.k / split_rows + 1 < (size_t)kMaxSplitParts && L.mt_dwd < 256 && L.mt_dwgu < 256;
+}
 
 static std::mutex g_bwd_workers_mu;
 static int g_bwd_workers[kMaxDevices * 2];   // filled on first use under the lock, constant afterwards
@@ -718,7 +849,7 @@ int bwd_launch(const moe_shape_t& s, const void* dy, const void* x, const void* 
                const void* w_up, const void* w_down, const moe_routing_t& r, const char* gu,
                const char* h, const char* o, void* dx, void* dw_gate, void* dw_up, void* dw_down,
                float* dtopk_w, char* ws, const moe_opts_t& opts, int nw, hipStream_t st) {
-    const BwdLayout L = bwd_layout(s);
+    const BwdLayout L = bwd_layout(s, opts.dw_split_rows);
     BwdParams p;
     p.s = s;
     p.dy = (const char*)dy;
@@ -748,6 +879,11 @@ int bwd_launch(const moe_shape_t& s, const void* dy, const void* x, const void* 
     p.dxp = ws + L.dxp;
     p.hw = ws + L.hw;
     p.dots = (float*)(ws + L.dots);
+    p.split_rows = opts.dw_split_rows;
+    p.split_base = (int32_t*)(ws + L.split_base);
+    p.split_tile0 = (int32_t*)(ws + L.split_tile0);
+    p.split_cnt = (int32_t*)(ws + L.split_cnt);
+    p.split_buf = ws + L.split_buf;
     p.n_dots = 4 * L.nct_dh;
     p.nct_dh = L.nct_dh;
     p.nct_dxp = L.nct_dxp;

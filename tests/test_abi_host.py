@@ -107,15 +107,29 @@ def test_null_and_misaligned_pointers_are_rejected_before_any_launch(lib):
     assert fwd(opts=ctypes.byref(bad)) == b.MOE_ERR_ARG
     bad = b.make_opts(dw_accumulate=2)
     assert fwd(opts=ctypes.byref(bad)) == b.MOE_ERR_ARG
-    for i in range(2):
-        bad = b.make_opts()
-        bad.reserved[i] = 1
+    for split in (-64, 100, 128, 300):   # negative, not a multiple of 64, below 256
+        bad = b.make_opts(dw_split_rows=split)
         assert fwd(opts=ctypes.byref(bad)) == b.MOE_ERR_ARG
+    bad = b.make_opts()
+    bad.reserved[0] = 1
+    assert fwd(opts=ctypes.byref(bad)) == b.MOE_ERR_ARG
     assert ctypes.sizeof(b.MoEOpts) == 32
     # backward needs the stash
     rc = lib.moe_fused_backward(ctypes.byref(s), fake, fake, fake, fake, fake, ctypes.byref(r_ok),
                                 None, fake, fake, fake, fake, None, fake, big, None, None)
     assert rc == b.MOE_ERR_ARG
+    # split weight-gradient reductions need the larger workspace that their own query reports
+    stash = ctypes.c_void_p(0x2000)
+    split = b.make_opts(dw_split_rows=256)
+    assert b.moe_backward_workspace_bytes(s, split) == b.moe_workspace_bytes(s)["bwd"]   # 16 rows: nothing to split
+    s = b.make_shape(T=512, d=64, E=8, k=2, I=64)
+    base = b.moe_workspace_bytes(s)["bwd"]
+    need = b.moe_backward_workspace_bytes(s, split)
+    assert need > base and b.moe_backward_workspace_bytes(s, None) == base
+    rc = lib.moe_fused_backward(ctypes.byref(s), fake, fake, fake, fake, fake, ctypes.byref(r_ok),
+                                stash, fake, fake, fake, fake, None, fake, ctypes.c_size_t(base),
+                                ctypes.byref(split), None)
+    assert rc == b.MOE_ERR_WORKSPACE
 
 
 def test_calibration_copy_rejects_bad_arguments(lib):

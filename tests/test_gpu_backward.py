@@ -16,7 +16,7 @@ GRAD_REL_L2 = 1e-2   # the benchmark spec tolerance for gradients
 KEYS = ("dx", "dw_gate", "dw_up", "dw_down")
 
 
-def gpu_fwd_bwd(cfg, inp, schedule, tile_rows, workers=0, want_dtopk_w=True):
+def gpu_fwd_bwd(cfg, inp, schedule, tile_rows, workers=0, want_dtopk_w=True, split=0):
     import paper_2604_19241_amd as moe
     shape = moe.make_shape(**cfg.shape_dict())
     dev = {key: v.cuda() for key, v in inp.items()}
@@ -24,9 +24,10 @@ def gpu_fwd_bwd(cfg, inp, schedule, tile_rows, workers=0, want_dtopk_w=True):
     saved = moe.alloc_saved(shape, "cuda")
     sizes = moe.moe_workspace_bytes(shape)
     ws = torch.empty(sizes["fwd"], dtype=torch.uint8, device="cuda")
-    wsb = torch.empty(sizes["bwd"], dtype=torch.uint8, device="cuda")
     opts = moe.make_opts(schedule=schedule, tile_rows=tile_rows, workers=workers,
-                         spin_limit_ms=500)
+                         spin_limit_ms=500, dw_split_rows=split)
+    wsb = torch.empty(moe.moe_backward_workspace_bytes(shape, opts), dtype=torch.uint8, device="cuda")
+    assert split or wsb.numel() == sizes["bwd"]
     moe.moe_fused_forward(shape, dev["x"], dev["w_gate"], dev["w_up"], dev["w_down"], routing,
                           saved=saved, ws=ws, opts=opts)
     g = moe.moe_fused_backward(shape, dev["dy"], dev["x"], dev["w_gate"], dev["w_up"],
@@ -224,3 +225,59 @@ def test_backward_accumulates_weight_gradients_in_fp32(schedule, tile_rows):
         assert torch.equal(got[key][busy], want[key][busy]), key
         for e in idle:
             assert torch.equal(got[key][e].view(torch.int32), main[key][e].view(torch.int32)), (key, e)
+
+
+@pytest.mark.parametrize("split", [256, 512])
+def test_backward_split_weight_gradient_reduction(split):
+    """opts.dw_split_rows: the weight-gradient reduction of an expert with more rows than that is
+    cut at fixed points and its partial tiles are added in part order.  Experts at or below the
+    threshold, dX and dtopk_w are bitwise what the unsplit call gives; the split experts agree with
+    the oracle to the same element-wise bounds; the result is bitwise the same from run to run,
+    across schedules, worker counts and tile heights; a threshold no expert exceeds changes nothing;
+    the fp32-accumulate form rounds to the same bf16 values."""
+    import paper_2604_19241_amd as moe
+    cfg = moe_synth.small_config(T=1500, d=320, E=6, k=2, I=320)
+    inp = scaled_inputs(cfg, 51, 4.0)
+    inp["logits"][:, 2] += 2.0      # one expert takes nearly every token, a second one about a third
+    inp["logits"][:, 4] += 0.6
+    inp["logits"][:, 5] = -30.0     # and one takes none
+    r = oracle.route(cfg.shape_dict(), inp["logits"].numpy())
+    counts = r["counts"]
+    say(f"[bwd split {split}] rows per expert {counts.tolist()}")
+    assert counts.max() > 2 * split and (counts == 0).any() and ((counts > 0) & (counts <= split)).any()
+    plain, _ = gpu_fwd_bwd(cfg, inp, 0, 0)
+    got, _ = gpu_fwd_bwd(cfg, inp, 0, 0, split=split)
+    assert torch.equal(got["dx"], plain["dx"]) and torch.equal(got["dtopk_w"], plain["dtopk_w"])
+    small = [int(e) for e in np.nonzero(counts <= split)[0]]
+    big = [int(e) for e in np.nonzero(counts > split)[0]]
+    b = bits(inp, ("x", "dy", "w_gate", "w_up", "w_down"))
+    want = oracle.backward(cfg.shape_dict(), b["x"], b["dy"], b["w_gate"], b["w_up"], b["w_down"], r,
+                           round_bf16=True, acc="f32")
+    for key in ("dw_gate", "dw_up", "dw_down"):
+        assert torch.equal(got[key][small], plain[key][small]), key
+        err = rel_l2(to_f64(got[key]), want[key])
+        differ = float((got[key][big] != plain[key][big]).float().mean())
+        say(f"   {key} rel_l2={err:.2e}; elements of the split experts that differ from the unsplit sum: {differ:.3f}")
+        assert err <= GRAD_REL_L2, (key, err)
+        check_elementwise(key, to_f64(got[key]), want[key])
+    ref = {k: v.clone() for k, v in got.items()}
+    for schedule, workers, tile_rows in ((0, 0, 0), (2, 0, 0), (1, 0, 0), (3, 3, 0), (1, 64, 0), (0, 0, 128)):
+        other, _ = gpu_fwd_bwd(cfg, inp, schedule, tile_rows, workers=workers, split=split)
+        for key in ref:
+            assert torch.equal(ref[key], other[key]), (key, schedule, workers, tile_rows)
+    same, _ = gpu_fwd_bwd(cfg, inp, 0, 0, split=4096)   # no expert has that many rows
+    for key in ref:
+        assert torch.equal(same[key], plain[key]), key
+    # added to fp32 buffers
+    shape = moe.make_shape(**cfg.shape_dict())
+    dev = {key: v.cuda() for key, v in inp.items()}
+    routing = moe.moe_route(shape, dev["logits"])
+    saved = moe.alloc_saved(shape, "cuda")
+    moe.moe_fused_forward(shape, dev["x"], dev["w_gate"], dev["w_up"], dev["w_down"], routing, saved=saved)
+    opts = moe.make_opts(spin_limit_ms=500, dw_accumulate=1, dw_split_rows=split)
+    out = {"dx": torch.empty_like(dev["x"]), "dtopk_w": None}
+    out.update({key: torch.zeros_like(dev["w_" + key[3:]], dtype=torch.float32) for key in ("dw_gate", "dw_up", "dw_down")})
+    acc = moe.moe_fused_backward(shape, dev["dy"], dev["x"], dev["w_gate"], dev["w_up"], dev["w_down"],
+                                 routing, saved, opts=opts, out=out, want_dtopk_w=False)
+    for key in ("dw_gate", "dw_up", "dw_down"):
+        assert torch.equal(acc[key].to(torch.bfloat16), ref[key]), key
