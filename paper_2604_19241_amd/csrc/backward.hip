@@ -380,7 +380,7 @@ __device__ __forceinline__ void accumulate8(float* q, const f32x16_t& a, int vg)
 
 // ------------------------------------------------------------- split weight-gradient reductions
 // One part of a split reduction ends here: the fp32 accumulators go to the part's slot in
-// accumulator layout (every store instruction writes 1 KB of consecutive bytes), the tile's
+// accumulator layout (every store instruction writes 512 consecutive bytes), the tile's
 // counter is advanced, and the workgroup that finds all other parts already counted adds the
 // `parts` partial tiles in the order of the part index, starting from zero: the sum does not
 // depend on which workgroup adds, nor on the order in which the parts were computed.
@@ -388,9 +388,10 @@ __device__ __forceinline__ void accumulate8(float* q, const f32x16_t& a, int vg)
 __device__ __forceinline__ bool finish_part(const BwdParams& p, int e, int tile, int part, int parts,
                                             f32x16_t (&acc)[4][2], int* s_flag) {
     if (parts <= 1) return true;
-    typedef __attribute__((ext_vector_type(4))) float f32x4_t;
     const Lane ln;
-    const size_t lane_off = (size_t)ln.w * 32768 + (size_t)ln.l * 16;
+    // 8-byte write-through stores: the two halves of a register quad go to separate 512-byte runs,
+    // so that every store instruction of a wave writes consecutive bytes
+    const size_t lane_off = (size_t)ln.w * 32768 + (size_t)ln.l * 8;
     char* slots = p.split_buf + ((size_t)p.split_base[e] + (size_t)tile * parts) * kPartialTileBytes;
     char* mine = slots + (size_t)part * kPartialTileBytes + lane_off;
 #pragma unroll
@@ -399,8 +400,11 @@ __device__ __forceinline__ bool finish_part(const BwdParams& p, int e, int tile,
         for (int af = 0; af < 2; ++af)
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const f32x4_t v = {acc[tf][af][4 * q], acc[tf][af][4 * q + 1], acc[tf][af][4 * q + 2], acc[tf][af][4 * q + 3]};
-                store_wt16(mine + ((tf * 2 + af) * 4 + q) * 1024, __builtin_bit_cast(u32x4_t, v));
+                const f32x2_t lo = {acc[tf][af][4 * q], acc[tf][af][4 * q + 1]};
+                const f32x2_t hi = {acc[tf][af][4 * q + 2], acc[tf][af][4 * q + 3]};
+                char* dst = mine + ((tf * 2 + af) * 4 + q) * 1024;
+                store_wt8(dst, __builtin_bit_cast(u32x2_t, lo));
+                store_wt8(dst + 512, __builtin_bit_cast(u32x2_t, hi));
             }
     wait_stores();
     __syncthreads();   // the partial tile of every wave has reached memory
@@ -426,11 +430,12 @@ __device__ __forceinline__ bool finish_part(const BwdParams& p, int e, int tile,
             for (int af = 0; af < 2; ++af)
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    const f32x4_t v = *(const f32x4_t*)(src + ((tf * 2 + af) * 4 + q) * 1024);
-                    acc[tf][af][4 * q] += v[0];
-                    acc[tf][af][4 * q + 1] += v[1];
-                    acc[tf][af][4 * q + 2] += v[2];
-                    acc[tf][af][4 * q + 3] += v[3];
+                    const char* blk = src + ((tf * 2 + af) * 4 + q) * 1024;
+                    const f32x2_t lo = *(const f32x2_t*)blk, hi = *(const f32x2_t*)(blk + 512);
+                    acc[tf][af][4 * q] += lo[0];
+                    acc[tf][af][4 * q + 1] += lo[1];
+                    acc[tf][af][4 * q + 2] += hi[0];
+                    acc[tf][af][4 * q + 3] += hi[1];
                 }
     }
     return true;
