@@ -465,7 +465,8 @@ struct WaveRepack {
     char* base;   // this wave's 16 KB
     int l;        // lane
     __device__ __forceinline__ WaveRepack(char* smem, const Lane& ln) : base(smem + ln.w * 16384), l(ln.l) {}
-    static __device__ __forceinline__ int swz(int row) { return NP == 8 ? ((row >> 1) & 7) : ((row >> 2) & 3); }
+    // eight neighbouring lanes of a put() hold eight consecutive rows: their 16-byte slots must differ
+    static __device__ __forceinline__ int swz(int row) { return NP == 8 ? (row & 7) : ((row >> 1) & 3); }
     // piece pi (0..NP-1) of sub-tile row `row` (0..127)
     __device__ __forceinline__ void put(int row, int pi, u32x4_t v) {
         *(u32x4_t*)(base + row * (NP * 16) + ((pi ^ swz(row)) << 4)) = v;
