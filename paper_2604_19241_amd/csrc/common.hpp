@@ -31,21 +31,13 @@ __device__ __forceinline__ float bf16_hi(uint32_t u) { return __uint_as_float(u 
 
 // ---- scoreboard primitives (agent scope: visible across all 8 XCDs' L2s)
 __device__ __forceinline__ int ld_acquire(const int* p) {
-#ifdef UNIEP_NO_ACQUIRE   // timing experiments only
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-#else
     return __hip_atomic_load(p, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
-#endif
 }
 __device__ __forceinline__ int ld_relaxed(const int* p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ __forceinline__ void add_release(int* p, int v) {
-#ifdef UNIEP_X_NORELEASE   // timing experiments only
-    __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-#else
     __hip_atomic_fetch_add(p, v, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
-#endif
 }
 
 // Write-through stores (agent scope): the data goes past this XCD's L2 to the
@@ -66,11 +58,7 @@ __device__ __forceinline__ void store_wt16(void* p, u32x4_t v) {
 // Streaming store for outputs that are written once and not read again soon
 // (o, the G|U stash, dXp, dW, y, dX): they should not displace operands in L2.
 __device__ __forceinline__ void store_stream16(void* p, u32x4_t v) {
-#ifdef UNIEP_X_NOSTREAM
-    *(u32x4_t*)p = v;
-#else
     __builtin_nontemporal_store(v, (u32x4_t*)p);
-#endif
 }
 // All write-through stores of this wave have completed.
 __device__ __forceinline__ void wait_stores() { asm volatile("s_waitcnt vmcnt(0)" : : : "memory"); }
@@ -293,9 +281,6 @@ __device__ __forceinline__ void queue_positions(const ListPlan& plan, const int*
 // consumer's inputs are complete when it is fetched, also near the end of the
 // lists, where stealing workgroups drain the consumer blocks quickly.
 __device__ __forceinline__ int queue_lag(int total_producer_tasks, int ec) {
-#ifdef UNIEP_X_LAG
-    return UNIEP_X_LAG;
-#endif
     const int per = max(1, total_producer_tasks / max(1, ec));
     return min(16, max(1, (128 + per - 1) / per));
 }
@@ -304,9 +289,7 @@ __device__ __forceinline__ int queue_lag(int total_producer_tasks, int ec) {
 // the bound is exceeded or another worker already raised it, so that every
 // wave leaves the kernel in finite time whatever happens.
 __device__ __forceinline__ void fence_acquire() {
-#ifndef UNIEP_NO_ACQUIRE
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-#endif
 }
 // The polls are relaxed loads; the one acquire fence follows the successful
 // poll.  An acquire per poll would invalidate this XCD's L2 at the polling

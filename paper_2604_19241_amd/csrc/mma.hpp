@@ -235,6 +235,7 @@ struct KcLoader {
     int n = 4;   // wave-uniform
     __device__ __forceinline__ void sync() {}
     // blocks of this wave that hold rows of a tile with `rows` rows
+    __device__ __forceinline__ void prepare() {}
     static __device__ __forceinline__ int blocks_for(const Lane& ln, int rows) {
         return min(4, max(0, (rows - 32 * ln.wave_uniform() + 7) >> 3));
     }
@@ -253,6 +254,7 @@ struct KcSplitLoader {
     const char* p[4];
     long long delta;   // (second matrix) - (first matrix) - (bytes walked in the first)
     int left;
+    __device__ __forceinline__ void prepare() {}
     __device__ __forceinline__ void sync() {}
     __device__ __forceinline__ void issue(char* dst) {
         char* d = dst + wave_block_off();
@@ -279,6 +281,7 @@ struct KsGeom {
 struct KsLoader {
     const char* p[4];
     long long step;   // 64 memory rows
+    __device__ __forceinline__ void prepare() {}
     __device__ __forceinline__ void sync() {}
     __device__ __forceinline__ void issue(char* dst) {
         char* d = dst + wave_block_off();
@@ -305,6 +308,7 @@ struct KsTailLoader {
     long long ld_bytes;   // one memory row (wave-uniform)
     int k0;               // reduction index of instruction 0's k row in the stage to come
     int K;
+    __device__ __forceinline__ void prepare() {}
     __device__ __forceinline__ void sync() {}
     __device__ __forceinline__ void issue(char* dst) {
         char* d = dst + wave_block_off();
@@ -322,12 +326,18 @@ struct KsTailLoader {
 // row indices of a stage are fetched (plain loads) right behind the DMA of the stage before
 // it and are complete by the barrier in between.  init() is called once per tile, after
 // coloff[] is filled.
+// prepare() turns the fetched indices into the four source addresses, and the main loop calls
+// it for both loaders before either requests anything: while a DMA is pending the compiler puts
+// a full vmcnt(0) in front of every use of a register that an ordinary load filled (it cannot
+// order the two kinds of operation), so address arithmetic between the DMA instructions would
+// make every request wait for the one before it to land.
 struct KsGatherLoader {
     const char* src;          // matrix base
     uint32_t coloff[2];       // byte offset, inside a memory row, of the chunk instructions i, i % 2 = j move
     long long ld_bytes;       // wave-uniform
     const int32_t* rows;      // row_tok + first row of the expert (wave-uniform)
     int32_t tok[4];           // memory rows of the stage whose DMA goes out next
+    const char* a[4];         // their addresses (prepare)
     int k0;                   // reduction index of instruction 0's k row in that stage
     int K;
     __device__ __forceinline__ void fetch() {
@@ -342,12 +352,18 @@ struct KsGatherLoader {
         k0 = KsGeom::krow(ln, 0);
         fetch();
     }
-    __device__ __forceinline__ void sync() {}
+    __device__ __forceinline__ void prepare() {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            a[i] = src + (long long)tok[i] * ld_bytes + coloff[i & 1];
+            asm volatile("" : "+v"(a[i]));   // the address exists before the first request
+        }
+    }
     __device__ __forceinline__ void issue(char* dst) {
         char* d = dst + wave_block_off();
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            if (k0 + 2 * i < K) dma16(src + (long long)tok[i] * ld_bytes + coloff[i & 1], d + i * 1024);
+            if (k0 + 2 * i < K) dma16(a[i], d + i * 1024);
             else lds_zero16(d + i * 1024);
         }
         k0 += BK;
@@ -368,11 +384,17 @@ template <int NTF, bool A_KS, bool B_KS, class LB, class LA>
 __device__ __forceinline__ void mma_loop(LB& lb, LA& la, int nk, char* smem, const FragAddr& fa,
                                          f32x16_t (&acc)[4][2]) {
     constexpr int NR = reads_per_step<NTF, A_KS, B_KS>();
+    lb.prepare();
+    la.prepare();
+    __builtin_amdgcn_sched_barrier(0);
     lb.issue(smem);
     la.issue(smem + kOperandBytes);
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();
     if (nk > 1) {
+        lb.prepare();
+        la.prepare();
+        __builtin_amdgcn_sched_barrier(0);
         lb.issue(smem + kStageBytes);
         la.issue(smem + kStageBytes + kOperandBytes);
     }
@@ -403,6 +425,9 @@ __device__ __forceinline__ void mma_loop(LB& lb, LA& la, int nk, char* smem, con
             asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
             __builtin_amdgcn_s_barrier();
             if (t + 2 < nk) {
+                lb.prepare();
+                la.prepare();
+                __builtin_amdgcn_sched_barrier(0);
                 lb.issue(smem + boff);
                 la.issue(smem + boff + kOperandBytes);
             }
