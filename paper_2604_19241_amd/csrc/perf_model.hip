@@ -68,51 +68,80 @@ Derived derive(const moe_perf_problem_t& p) {
     return d;
 }
 
-// B(n, beta) = min(n w beta / w_sat, beta)
-double eff_bw(int n, double beta, int w, int w_sat) { return std::fmin(n * (double)w * beta / w_sat, beta); }
+// ---- the model, as two kinds of table entry ------------------------------------------------
+// The latency of a configuration is (entry of stage 1) + (entry of stage 2) + a constant.  A
+// stage-1 entry depends on (N_disp, N_relay, w), a stage-2 entry on (N_comb, N_red, w), and
+// nothing couples the two.  Both moe_perf_model_eval and the search are built on the entry
+// constructors below: eval makes the two entries of its configuration, the search makes every
+// entry once and walks the pairs.  Each constructor states the scheduling picture the
+// equations of Section 4.2 describe; the fp64 expressions keep the printed association so that
+// both agree with a term-by-term evaluation to the last bit.
 
-double t_gemm(const moe_perf_hw_t& h, const moe_perf_problem_t& p, int k_dim, int w) {
+// Copy rate that n workers of w warps reach on a path of rate beta: linear in the warps in
+// flight until w_sat of them saturate it.
+double copy_rate(int n, double beta, int w, int w_sat) { return std::fmin(n * (double)w * beta / w_sat, beta); }
+
+// One tile of b_m x b_n over a reduction of k_dim on one worker's share of the matrix rate
+// (scaled by the efficiency mu of that warp count), plus the per-tile synchronisation.
+double tile_time(const moe_perf_hw_t& h, const moe_perf_problem_t& p, int k_dim, int w) {
     const double mu = h.mu[warp_slot(w)];
     return 2.0 * p.b_m * p.b_n * k_dim / (h.p_peak * (mu / h.n_sm)) + h.tau_sync;
 }
 
-double l_comp(int64_t tiles, double t_block, int n_comp) {
-    return (double)((tiles + n_comp - 1) / n_comp) * t_block;
+// `tiles` tiles in waves over n workers.
+double tiles_on(int64_t tiles, double per_tile, int n) { return (double)((tiles + n - 1) / n) * per_tile; }
+
+struct Stage1Entry {   // tokens arrive (link copy + relay copies) while the up GEMM consumes them
+    double arrive, gemm, total;
+};
+Stage1Entry stage1_entry(const moe_perf_hw_t& h, const Derived& d, int n_disp, int n_relay, int w, double up_tile) {
+    Stage1Entry e;
+    const int gemm_workers = h.n_sm - n_disp;
+    e.arrive = d.v_nvl / copy_rate(n_disp, h.beta_link, w, h.w_sat) +
+               d.v_hbm_disp / copy_rate(n_relay, h.beta_hbm, w, h.w_sat);
+    e.gemm = tiles_on(d.tiles_up, up_tile, gemm_workers);
+    // GEMM outlasts the copies: what is left of it when they end continues on every worker.
+    // Copies outlast the GEMM: one more tile after the last token.
+    e.total = (e.gemm > e.arrive) ? e.arrive + (e.gemm - e.arrive) * h.n_sm / gemm_workers : e.arrive + up_tile;
+    return e;
 }
 
-// Stage 1 of Algorithm 2: dispatch overlapped with the up GEMM.
-void stage1(const moe_perf_hw_t& h, const moe_perf_problem_t& p, const Derived& d, int n_disp, int n_relay,
-            int w, double t_up, double* l_disp, double* l_up, double* l_s1) {
-    const int n_comp1 = h.n_sm - n_disp;
-    *l_disp = d.v_nvl / eff_bw(n_disp, h.beta_link, w, h.w_sat) +
-              d.v_hbm_disp / eff_bw(n_relay, h.beta_hbm, w, h.w_sat);
-    *l_up = l_comp(d.tiles_up, t_up, n_comp1);
-    if (*l_up > *l_disp) *l_s1 = *l_disp + (*l_up - *l_disp) * h.n_sm / n_comp1;
-    else *l_s1 = *l_disp + t_up;
-    (void)p;
+struct Stage2Entry {   // down GEMM next to the combine copies; the reduce fills idle worker time
+    double leave, one_reducer, gemm, total;
+};
+Stage2Entry stage2_entry(const moe_perf_hw_t& h, const Derived& d, int n_comb, int n_red, int w, double down_tile) {
+    Stage2Entry e;
+    const int gemm_workers = h.n_sm - n_comb;
+    e.leave = d.v_nvl / copy_rate(n_comb, h.beta_link, w, h.w_sat);
+    e.one_reducer = d.v_hbm_total / copy_rate(1, h.beta_hbm, w, h.w_sat);
+    e.gemm = tiles_on(d.tiles_down, down_tile, gemm_workers);
+    // Whichever of the two ends first leaves its workers idle for the difference; reduce work
+    // beyond that idle worker-time is spread over all workers.
+    const double idle_worker_time = std::fabs(e.gemm - e.leave) * gemm_workers;
+    const double reduce_work = n_red * e.one_reducer;
+    e.total = std::fmax(e.gemm, e.leave) + std::fmax(0.0, reduce_work - idle_worker_time) / h.n_sm;
+    return e;
 }
 
-// Stage 2: down GEMM overlapped with the combine; the reduce fills the gap between the two.
-void stage2(const moe_perf_hw_t& h, const Derived& d, int n_comb, int n_red, int w, double t_down,
-            double* l_comb, double* t_red, double* l_down, double* l_s2) {
-    const int n_comp2 = h.n_sm - n_comb;
-    *l_comb = d.v_nvl / eff_bw(n_comb, h.beta_link, w, h.w_sat);
-    *t_red = d.v_hbm_total / eff_bw(1, h.beta_hbm, w, h.w_sat);
-    *l_down = l_comp(d.tiles_down, t_down, n_comp2);
-    const double l_base = std::fmax(*l_down, *l_comb);
-    const double w_gap = std::fabs(*l_down - *l_comb) * n_comp2;
-    const double w_red = n_red * *t_red;
-    const double w_rem = std::fmax(0.0, w_red - w_gap);
-    *l_s2 = l_base + w_rem / h.n_sm;
+// The part no configuration changes: SwiGLU as a pass over the routed activations.
+double swiglu_pass(const moe_perf_hw_t& h, const moe_perf_problem_t& p, const Derived& d) {
+    return 2.0 * p.n_tok * d.s_tok / h.beta_hbm;
 }
 
 void evaluate(const moe_perf_hw_t& h, const moe_perf_problem_t& p, const Derived& d,
               const moe_perf_config_t& c, moe_perf_latency_t* out) {
-    out->t_up = t_gemm(h, p, p.h_dim, c.warps);
-    out->t_down = t_gemm(h, p, p.h_inter, c.warps);
-    out->l_swiglu = 2.0 * p.n_tok * d.s_tok / h.beta_hbm;
-    stage1(h, p, d, c.n_disp, c.n_relay, c.warps, out->t_up, &out->l_disp, &out->l_up, &out->l_s1);
-    stage2(h, d, c.n_comb, c.n_red, c.warps, out->t_down, &out->l_comb, &out->t_red, &out->l_down, &out->l_s2);
+    out->t_up = tile_time(h, p, p.h_dim, c.warps);
+    out->t_down = tile_time(h, p, p.h_inter, c.warps);
+    const Stage1Entry a = stage1_entry(h, d, c.n_disp, c.n_relay, c.warps, out->t_up);
+    const Stage2Entry b = stage2_entry(h, d, c.n_comb, c.n_red, c.warps, out->t_down);
+    out->l_swiglu = swiglu_pass(h, p, d);
+    out->l_disp = a.arrive;
+    out->l_up = a.gemm;
+    out->l_s1 = a.total;
+    out->l_comb = b.leave;
+    out->t_red = b.one_reducer;
+    out->l_down = b.gemm;
+    out->l_s2 = b.total;
     out->l_total = out->l_s1 + out->l_s2 + out->l_swiglu;
 }
 
@@ -154,7 +183,7 @@ extern "C" int moe_perf_model_search(const moe_perf_hw_t* hw, const moe_perf_pro
     const Derived d = derive(p);
     const std::vector<int> comm = comm_choices(h.n_sm), red = reduce_choices(h.n_sm);
 
-    // Candidates of the two stages per warp count, each in the order the nested enumeration
+    // The two tables: every stage entry per warp count, each in the order the nested enumeration
     // (N_disp, N_relay, N_comb, N_red, w) meets them.
     struct S1 { int n_disp, n_relay; double l[3]; };
     struct S2 { int n_comb, n_red; double l[3]; };
@@ -163,18 +192,15 @@ extern "C" int moe_perf_model_search(const moe_perf_hw_t* hw, const moe_perf_pro
     int64_t enum1 = 0, enum2 = 0;
     double t_up[3], t_down[3];
     for (int wi = 0; wi < 3; ++wi) {
-        t_up[wi] = t_gemm(h, p, p.h_dim, kWarps[wi]);
-        t_down[wi] = t_gemm(h, p, p.h_inter, kWarps[wi]);
+        t_up[wi] = tile_time(h, p, p.h_dim, kWarps[wi]);
+        t_down[wi] = tile_time(h, p, p.h_inter, kWarps[wi]);
     }
     for (int n_disp : comm)
         for (int n_relay : relay_choices(n_disp)) {
             ++enum1;
             if (!(n_disp < h.n_sm && n_disp + n_relay < h.n_sm)) continue;
             S1 c{n_disp, n_relay, {0, 0, 0}};
-            for (int wi = 0; wi < 3; ++wi) {
-                double a, b;
-                stage1(h, p, d, n_disp, n_relay, kWarps[wi], t_up[wi], &a, &b, &c.l[wi]);
-            }
+            for (int wi = 0; wi < 3; ++wi) c.l[wi] = stage1_entry(h, d, n_disp, n_relay, kWarps[wi], t_up[wi]).total;
             s1.push_back(c);
         }
     for (int n_comb : comm)
@@ -182,10 +208,7 @@ extern "C" int moe_perf_model_search(const moe_perf_hw_t* hw, const moe_perf_pro
             ++enum2;
             if (!(n_comb < h.n_sm)) continue;
             S2 c{n_comb, n_red, {0, 0, 0}};
-            for (int wi = 0; wi < 3; ++wi) {
-                double a, b, e;
-                stage2(h, d, n_comb, n_red, kWarps[wi], t_down[wi], &a, &b, &e, &c.l[wi]);
-            }
+            for (int wi = 0; wi < 3; ++wi) c.l[wi] = stage2_entry(h, d, n_comb, n_red, kWarps[wi], t_down[wi]).total;
             s2.push_back(c);
         }
     if (n_enumerated) *n_enumerated = enum1 * enum2 * 3;
@@ -197,7 +220,7 @@ extern "C" int moe_perf_model_search(const moe_perf_hw_t* hw, const moe_perf_pro
     // would compare.  The space is small enough (about 1e5 sums) to compare every pair, which
     // keeps the tie rule of Algorithm 2 (first strictly smaller total in enumeration order)
     // without any argument about rounding: walk the pairs in enumeration order.
-    const double l_sw = 2.0 * p.n_tok * d.s_tok / h.beta_hbm;
+    const double l_sw = swiglu_pass(h, p, d);
     double l_min = std::numeric_limits<double>::infinity();
     size_t bi = 0, bj = 0;
     int bw = 0;
