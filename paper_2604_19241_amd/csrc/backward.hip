@@ -444,7 +444,7 @@ __device__ __forceinline__ bool finish_part(const BwdParams& p, int e, int tile,
 // ------------------------------------------------------------- phase 1: dW_down
 // dW_down[e][i][c] = sum over the expert's rows r (ascending) of (gate_r h[r][i]) * dY[tok_r][c].
 // Output tile: 256 rows of I by 256 columns of d; both operands have k = r as their memory row.
-template <bool ACC, class Hook>
+template <bool ACC, bool SPLIT, class Hook>
 __device__ __forceinline__ void dwd_task(const BwdParams& p, int e, int idx, int nt, int r0, int cnt,
                                          char* smem, int* s_flag, Hook after_mainloop) {
     const int mt = wgrad_mt(idx);
@@ -467,7 +467,7 @@ __device__ __forceinline__ void dwd_task(const BwdParams& p, int e, int idx, int
     f32x16_t acc[4][2];
     mma_tile<true, true>(lb, la, (cnt + BK - 1) / BK, min(BMAX, I - m0), smem, fa, acc);
     after_mainloop();
-    if (!finish_part(p, e, p.mt_dwgu * p.nt_dwgu + mt * p.nt_dwd + nt, wgrad_part(idx), wgrad_parts(idx), acc, s_flag)) return;
+    if (SPLIT && !finish_part(p, e, p.mt_dwgu * p.nt_dwgu + mt * p.nt_dwd + nt, wgrad_part(idx), wgrad_parts(idx), acc, s_flag)) return;
     if (ACC) {
         const Lane le;
 #pragma unroll
@@ -495,7 +495,7 @@ __device__ __forceinline__ void dwd_task(const BwdParams& p, int e, int idx, int
 // dW_gate[e][c][i] = sum_r x[tok(r)][c] * dG[r][i]; dW_up likewise with dU.
 // Output tile: 256 rows of d by 128 columns of I, for both matrices at once: column fragment 0
 // of a wave holds dG columns, fragment 1 the same dU columns.
-template <bool ACC, class Hook>
+template <bool ACC, bool SPLIT, class Hook>
 __device__ __forceinline__ void dwgu_task(const BwdParams& p, int e, int idx, int nt, int r0, int cnt,
                                           char* smem, int* s_flag, Hook after_mainloop) {
     const int mt = wgrad_mt(idx);
@@ -520,7 +520,7 @@ __device__ __forceinline__ void dwgu_task(const BwdParams& p, int e, int idx, in
     f32x16_t acc[4][2];
     mma_tile<true, true>(lb, la, (cnt + BK - 1) / BK, min(BMAX, d - m0), smem, fa, acc);
     after_mainloop();
-    if (!finish_part(p, e, mt * p.nt_dwgu + nt, wgrad_part(idx), wgrad_parts(idx), acc, s_flag)) return;
+    if (SPLIT && !finish_part(p, e, mt * p.nt_dwgu + nt, wgrad_part(idx), wgrad_parts(idx), acc, s_flag)) return;
     if (ACC) {
         const Lane le;
 #pragma unroll
@@ -616,7 +616,9 @@ __device__ __forceinline__ void dx_task(const BwdParams& p, int block) {
 
 // ------------------------------------------------------------- worker loop
 // ACC: the weight gradients are added to fp32 buffers (moe_opts_t.dw_accumulate).
-template <bool ACC>
+// SPLIT: weight-gradient tasks may be parts of a split reduction (moe_opts_t.dw_split_rows > 0); the
+// default kernel carries none of that code.
+template <bool ACC, bool SPLIT>
 __device__ __forceinline__ void bwd_worker_body(const BwdParams& p, int phase, char* smem) {
     __shared__ int s_task;
     __shared__ int s_ok;
@@ -676,13 +678,14 @@ __device__ __forceinline__ void bwd_worker_body(const BwdParams& p, int phase, c
                 // weight-gradient tiles read what ALL dH tiles of the expert wrote (dG|dU, gate * h):
                 // its row tiles times the dH column tiles
                 const int e = task_expert(task);
-                const int rows_e = p.offsets[e + 1] - p.offsets[e];   // (task.rows is the part's share)
+                // rows of the whole expert (a part of a split reduction carries only its own share)
+                const int rows_e = SPLIT ? p.offsets[e + 1] - p.offsets[e] : task.rows;
                 const int need = (rows_e + p.bm - 1) / p.bm * p.nct_dh;
                 if (threadIdx.x == 0) s_ok = wait_ge(p.flag_e + e, need, ctrl, p.spin_ticks);
                 __syncthreads();
                 if (s_ok) {
-                    if (type == B_DWD) dwd_task<ACC>(p, e, task.idx, ct, task.row0, task.rows, smem, &s_ok, issue);
-                    else dwgu_task<ACC>(p, e, task.idx, ct, task.row0, task.rows, smem, &s_ok, issue);
+                    if (type == B_DWD) dwd_task<ACC, SPLIT>(p, e, task.idx, ct, task.row0, task.rows, smem, &s_ok, issue);
+                    else dwgu_task<ACC, SPLIT>(p, e, task.idx, ct, task.row0, task.rows, smem, &s_ok, issue);
                 }
             }
         } else {
@@ -716,15 +719,21 @@ __device__ __forceinline__ void bwd_worker_body(const BwdParams& p, int phase, c
     }
 }
 
-__global__ void __launch_bounds__(kMmaThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
-bwd_worker_kernel(BwdParams p, int phase) {
-    extern __shared__ __attribute__((aligned(16))) char smem[];
-    bwd_worker_body<false>(p, phase, smem);
-}
-__global__ void __launch_bounds__(kMmaThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
-bwd_worker_acc_kernel(BwdParams p, int phase) {
-    extern __shared__ __attribute__((aligned(16))) char smem[];
-    bwd_worker_body<true>(p, phase, smem);
+#define UNIEP_BWD_WORKER(name, ACC, SPLIT)                                                         \
+    __global__ void __launch_bounds__(kMmaThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))       \
+    name(BwdParams p, int phase) {                                                                  \
+        extern __shared__ __attribute__((aligned(16))) char smem[];                                 \
+        bwd_worker_body<ACC, SPLIT>(p, phase, smem);                                                \
+    }
+UNIEP_BWD_WORKER(bwd_worker_kernel, false, false)
+UNIEP_BWD_WORKER(bwd_worker_acc_kernel, true, false)
+UNIEP_BWD_WORKER(bwd_worker_split_kernel, false, true)
+UNIEP_BWD_WORKER(bwd_worker_acc_split_kernel, true, true)
+#undef UNIEP_BWD_WORKER
+typedef void (*BwdWorkerFn)(BwdParams, int);
+static BwdWorkerFn bwd_worker_fn(bool acc, bool split) {
+    return split ? (acc ? bwd_worker_acc_split_kernel : bwd_worker_split_kernel)
+                 : (acc ? bwd_worker_acc_kernel : bwd_worker_kernel);
 }
 
 // dX (and dtopk_w) as a plain grid launch behind the GEMM MegaKernel, one workgroup per block
@@ -787,23 +796,20 @@ bool bwd_split_ok(const moe_shape_t& s, int split_rows) {
 }
 
 static std::mutex g_bwd_workers_mu;
-static int g_bwd_workers[kMaxDevices * 2];   // filled on first use under the lock, constant afterwards
+static int g_bwd_workers[kMaxDevices * 4];   // per device and kernel variant; filled on first use under the lock, constant afterwards
 
-template <bool ACC>
-static int bwd_resident_workers(int* out) {
+static int bwd_resident_workers(bool acc, bool split, int* out) {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return MOE_ERR_HIP;
-    const int slot = dev * 2 + (ACC ? 1 : 0);
+    const int slot = dev * 4 + (acc ? 1 : 0) + (split ? 2 : 0);
     std::lock_guard<std::mutex> lock(g_bwd_workers_mu);
     if (g_bwd_workers[slot] == 0) {
-        const void* fn = ACC ? (const void*)bwd_worker_acc_kernel : (const void*)bwd_worker_kernel;
-        if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kMmaSmem) != hipSuccess)
+        const BwdWorkerFn fn = bwd_worker_fn(acc, split);
+        if (hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, kMmaSmem) != hipSuccess)
             return MOE_ERR_HIP;
         int per_cu = 0, cus = 0;
-        const hipError_t occ = ACC
-            ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, bwd_worker_acc_kernel, kMmaThreads, kMmaSmem)
-            : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, bwd_worker_kernel, kMmaThreads, kMmaSmem);
-        if (occ != hipSuccess) return MOE_ERR_HIP;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kMmaThreads, kMmaSmem) != hipSuccess)
+            return MOE_ERR_HIP;
         if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
             return MOE_ERR_HIP;
         if (per_cu < 1 || cus < 1) return MOE_ERR_HIP;
@@ -813,18 +819,15 @@ static int bwd_resident_workers(int* out) {
     return MOE_OK;
 }
 
-template <bool ACC>
-static void launch_worker(const BwdParams& p, int workers, int phase, hipStream_t st) {
-    if (ACC)
-        hipLaunchKernelGGL(bwd_worker_acc_kernel, dim3(workers), dim3(kMmaThreads), kMmaSmem, st, p, phase);
-    else
-        hipLaunchKernelGGL(bwd_worker_kernel, dim3(workers), dim3(kMmaThreads), kMmaSmem, st, p, phase);
+static void launch_worker(bool acc, bool split, const BwdParams& p, int workers, int phase, hipStream_t st) {
+    hipLaunchKernelGGL(bwd_worker_fn(acc, split), dim3(workers), dim3(kMmaThreads), kMmaSmem, st, p, phase);
 }
 
-template <int BM, bool ACC>
+template <int BM>
 static int bwd_launch_bm(BwdParams& p, const moe_opts_t& opts, hipStream_t st) {
+    const bool acc = opts.dw_accumulate != 0, split = opts.dw_split_rows > 0;
     int resident = 0;
-    int rc = bwd_resident_workers<ACC>(&resident);
+    int rc = bwd_resident_workers(acc, split, &resident);
     if (rc != MOE_OK) return rc;
     const int workers = opts.workers > 0 ? min(opts.workers, resident) : resident;
     p.workers = workers;
@@ -834,9 +837,9 @@ static int bwd_launch_bm(BwdParams& p, const moe_opts_t& opts, hipStream_t st) {
         hipLaunchKernelGGL(row_meta_kernel, dim3((A_cap + 255) / 256), dim3(256), 0, st, p);
     hipLaunchKernelGGL(bwd_prologue_kernel<BM>, dim3(1), dim3(1024), 0, st, p);
     if (opts.schedule == 2) {
-        for (int phase = 0; phase < 5; ++phase) launch_worker<ACC>(p, workers, phase, st);
+        for (int phase = 0; phase < 5; ++phase) launch_worker(acc, split, p, workers, phase, st);
     } else if (opts.schedule != 1) {   // 0 (default) and 3: GEMM MegaKernel, then the tail tasks
-        launch_worker<ACC>(p, workers, -2, st);
+        launch_worker(acc, split, p, workers, -2, st);
         const int n_tail = (p.s.T + kDxTokens - 1) / kDxTokens;
         if (n_tail > 0 && !opts.skip_tail) {
             if (p.s.k <= 8)
@@ -845,7 +848,7 @@ static int bwd_launch_bm(BwdParams& p, const moe_opts_t& opts, hipStream_t st) {
                 hipLaunchKernelGGL((bwd_tail_kernel<8, kMaxTopK>), dim3(n_tail), dim3(kMmaThreads), 0, st, p);
         }
     } else {
-        launch_worker<ACC>(p, workers, -1, st);
+        launch_worker(acc, split, p, workers, -1, st);
     }
     return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
@@ -898,9 +901,7 @@ int bwd_launch(const moe_shape_t& s, const void* dy, const void* x, const void* 
     p.nt_dwgu = L.nt_dwgu;
     const int ms = opts.spin_limit_ms > 0 ? opts.spin_limit_ms : 2000;
     p.spin_ticks = (long long)ms * 100000ll;
-    if (opts.dw_accumulate)
-        return nw == 4 ? bwd_launch_bm<128, true>(p, opts, st) : bwd_launch_bm<256, true>(p, opts, st);
-    return nw == 4 ? bwd_launch_bm<128, false>(p, opts, st) : bwd_launch_bm<256, false>(p, opts, st);
+    return nw == 4 ? bwd_launch_bm<128>(p, opts, st) : bwd_launch_bm<256>(p, opts, st);
 }
 
 }  // namespace uniep
