@@ -117,6 +117,9 @@ __device__ __forceinline__ int fetch_task(int* ctrl, int pass, int home, unsigne
                                           bool use_lists, bool use_tail) {
     int* cur = ctrl + CTRL_CURSOR + pass * (kQueues + 1);
     if (use_lists) {
+        // (not unrolled: `home` is fixed for the kernel, and eight precomputed cursor addresses
+        // would occupy registers, or scratch, across the worker's whole loop)
+#pragma unroll 1
         for (int i = 0; i < kQueues; ++i) {
             const int q = (home + i) & (kQueues - 1);
             if (exhausted & (1u << q)) continue;
@@ -147,14 +150,14 @@ __device__ __forceinline__ PendingFetch fetch_issue(int* ctrl, int pass, int hom
     PendingFetch f;
     f.q = -1;
     f.id = 0;
-    if (use_lists) {
-        for (int i = 0; i < kQueues; ++i) {
-            const int q = (home + i) & (kQueues - 1);
-            if (exhausted & (1u << q)) continue;
-            f.q = q;
-            f.id = atomicAdd(ctrl + CTRL_CURSOR + pass * (kQueues + 1) + q, 1);
-            break;
-        }
+    // first list from `home` on (cyclically) that has not been seen empty: one computed address, so
+    // that the compiler does not keep eight cursor addresses alive across the worker's whole loop
+    const unsigned live = ~exhausted & ((1u << kQueues) - 1u);
+    if (use_lists && live != 0) {
+        const unsigned rot = ((live >> home) | (live << (kQueues - home))) & ((1u << kQueues) - 1u);
+        const int q = (home + __builtin_ctz(rot)) & (kQueues - 1);
+        f.q = q;
+        f.id = atomicAdd(ctrl + CTRL_CURSOR + pass * (kQueues + 1) + q, 1);
     }
     return f;
 }
