@@ -205,6 +205,57 @@ __device__ __forceinline__ void mfma_step(const Frags& f, f32x16_t (&acc)[4][2])
                                                                   acc[tf][af], 0, 0, 0);
 }
 
+// The matrix instructions of one k-sub-step (fragments `cur`) with the fragment reads of sub-step KK
+// (into `nxt`) between the first three of them: a wave issues in order, and a matrix instruction
+// keeps its pipe busy for 32 clocks during which the same wave may issue other instructions, so
+// the reads cost no matrix issue slot, and the LDS sees them spread out instead of in bursts of
+// six to twelve from every wave at once.
+template <int NTF, bool A_KS, bool B_KS, int KK>
+__device__ __forceinline__ void mfma_step_reading(const Frags& cur, Frags& nxt, const FragAddr& fa, uint32_t boff,
+                                                  f32x16_t (&acc)[4][2]) {
+    auto mm = [&](int tf, int af) {
+        acc[tf][af] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, cur.a[af]),
+                                                              __builtin_bit_cast(bf16x8_t, cur.b[tf]), acc[tf][af], 0, 0, 0);
+    };
+    const uint32_t ad = (A_KS ? 0u : fa.a[KK]) + boff, bd = (B_KS ? fa.b[0] : fa.b[KK]) + boff;
+    if (NTF > 0) mm(0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    if (A_KS) {
+        read_ks<KK>(nxt.a[0], fa.a[0] + boff);
+        read_ks<KK>(nxt.a[1], fa.a[1] + boff);
+    } else {
+        read_kc<0>(nxt.a[0], ad);
+        read_kc<1>(nxt.a[1], ad);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    if (NTF > 0) mm(0, 1);
+    __builtin_amdgcn_sched_barrier(0);
+    if (B_KS) {
+        if (NTF > 0) read_ks<KK>(nxt.b[0], bd + fa.b[1]);
+        if (NTF > 1) read_ks<KK>(nxt.b[1], bd + (fa.b[1] ^ 64u));
+    } else {
+        if (NTF > 0) read_kc<0>(nxt.b[0], bd);
+        if (NTF > 1) read_kc<1>(nxt.b[1], bd);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    if (NTF > 1) mm(1, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    if (B_KS) {
+        if (NTF > 2) read_ks<KK>(nxt.b[2], bd + (fa.b[1] ^ 128u));
+        if (NTF > 3) read_ks<KK>(nxt.b[3], bd + (fa.b[1] ^ 192u));
+    } else {
+        if (NTF > 2) read_kc<2>(nxt.b[2], bd);
+        if (NTF > 3) read_kc<3>(nxt.b[3], bd);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    if (NTF > 1) mm(1, 1);
+#pragma unroll
+    for (int tf = 2; tf < NTF; ++tf) {
+        mm(tf, 0);
+        mm(tf, 1);
+    }
+}
+
 __device__ __forceinline__ void wait_vmem() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 // ------------------------------------------------------------------ DMA sources
@@ -376,7 +427,8 @@ struct KsGatherLoader {
 // NTF = row fragments of this wave that hold rows of the tile (0..4): the others are neither
 // read nor multiplied.  Every wave takes part in the DMA and in the barriers whatever its NTF.
 // Pipeline per stage t (buffer t % 2), k-sub-steps 0..3 of 16:
-//   sub-step s < 3: request the fragments of s+1, wait for those of s, 8 matrix instructions;
+//   sub-step s < 3: wait for the fragments of s, 8 matrix instructions with the fragment reads
+//                   of s+1 between the first three of them (mfma_step_reading);
 //   sub-step 3:     wait for its fragments (the last reads of the buffer), wait for this wave's
 //                   DMA of stage t+1, barrier, request the row operand of stage t+2 into the
 //                   buffer just freed, request the fragments of (t+1, 0), 8 matrix instructions,
@@ -386,7 +438,6 @@ struct KsGatherLoader {
 template <int NTF, bool A_KS, bool B_KS, class LB, class LA>
 __device__ __forceinline__ void mma_loop(LB& lb, LA& la, int nk, char* smem, const FragAddr& fa,
                                          f32x16_t (&acc)[4][2]) {
-    constexpr int NR = reads_per_step<NTF, A_KS, B_KS>();
     lb.prepare();
     la.prepare();
     __builtin_amdgcn_sched_barrier(0);
@@ -407,20 +458,17 @@ __device__ __forceinline__ void mma_loop(LB& lb, LA& la, int nk, char* smem, con
         const uint32_t boff = (t & 1) * kStageBytes, noff = kStageBytes - boff;
         __builtin_amdgcn_sched_barrier(0);
         if (NTF > 0) {
-            read_frags<NTF, A_KS, B_KS, 1>(f1, fa, boff);
-            wait_frags<NR>(f0);
+            wait_frags<0>(f0);
             __builtin_amdgcn_sched_barrier(0);
-            mfma_step<NTF>(f0, acc);
+            mfma_step_reading<NTF, A_KS, B_KS, 1>(f0, f1, fa, boff, acc);
             __builtin_amdgcn_sched_barrier(0);
-            read_frags<NTF, A_KS, B_KS, 2>(f0, fa, boff);
-            wait_frags<NR>(f1);
+            wait_frags<0>(f1);
             __builtin_amdgcn_sched_barrier(0);
-            mfma_step<NTF>(f1, acc);
+            mfma_step_reading<NTF, A_KS, B_KS, 2>(f1, f0, fa, boff, acc);
             __builtin_amdgcn_sched_barrier(0);
-            read_frags<NTF, A_KS, B_KS, 3>(f1, fa, boff);
-            wait_frags<NR>(f0);
+            wait_frags<0>(f0);
             __builtin_amdgcn_sched_barrier(0);
-            mfma_step<NTF>(f0, acc);
+            mfma_step_reading<NTF, A_KS, B_KS, 3>(f0, f1, fa, boff, acc);
             __builtin_amdgcn_sched_barrier(0);
             wait_frags<0>(f1);
         }
