@@ -212,7 +212,7 @@ __device__ __forceinline__ void mfma_step(const Frags& f, f32x16_t (&acc)[4][2])
 // six to twelve from every wave at once.
 template <int NTF, bool A_KS, bool B_KS, int KK>
 __device__ __forceinline__ void mfma_step_reading(const Frags& cur, Frags& nxt, const FragAddr& fa, uint32_t boff,
-                                                  f32x16_t (&acc)[4][2]) {
+                                                  f32x16_t (&acc)[4][2], bool rd = true) {
     auto mm = [&](int tf, int af) {
         acc[tf][af] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, cur.a[af]),
                                                               __builtin_bit_cast(bf16x8_t, cur.b[tf]), acc[tf][af], 0, 0, 0);
@@ -220,32 +220,38 @@ __device__ __forceinline__ void mfma_step_reading(const Frags& cur, Frags& nxt, 
     const uint32_t ad = (A_KS ? 0u : fa.a[KK]) + boff, bd = (B_KS ? fa.b[0] : fa.b[KK]) + boff;
     if (NTF > 0) mm(0, 0);
     __builtin_amdgcn_sched_barrier(0);
-    if (A_KS) {
-        read_ks<KK>(nxt.a[0], fa.a[0] + boff);
-        read_ks<KK>(nxt.a[1], fa.a[1] + boff);
-    } else {
-        read_kc<0>(nxt.a[0], ad);
-        read_kc<1>(nxt.a[1], ad);
+    if (rd) {
+        if (A_KS) {
+            read_ks<KK>(nxt.a[0], fa.a[0] + boff);
+            read_ks<KK>(nxt.a[1], fa.a[1] + boff);
+        } else {
+            read_kc<0>(nxt.a[0], ad);
+            read_kc<1>(nxt.a[1], ad);
+        }
     }
     __builtin_amdgcn_sched_barrier(0);
     if (NTF > 0) mm(0, 1);
     __builtin_amdgcn_sched_barrier(0);
-    if (B_KS) {
-        if (NTF > 0) read_ks<KK>(nxt.b[0], bd + fa.b[1]);
-        if (NTF > 1) read_ks<KK>(nxt.b[1], bd + (fa.b[1] ^ 64u));
-    } else {
-        if (NTF > 0) read_kc<0>(nxt.b[0], bd);
-        if (NTF > 1) read_kc<1>(nxt.b[1], bd);
+    if (rd) {
+        if (B_KS) {
+            if (NTF > 0) read_ks<KK>(nxt.b[0], bd + fa.b[1]);
+            if (NTF > 1) read_ks<KK>(nxt.b[1], bd + (fa.b[1] ^ 64u));
+        } else {
+            if (NTF > 0) read_kc<0>(nxt.b[0], bd);
+            if (NTF > 1) read_kc<1>(nxt.b[1], bd);
+        }
     }
     __builtin_amdgcn_sched_barrier(0);
     if (NTF > 1) mm(1, 0);
     __builtin_amdgcn_sched_barrier(0);
-    if (B_KS) {
-        if (NTF > 2) read_ks<KK>(nxt.b[2], bd + (fa.b[1] ^ 128u));
-        if (NTF > 3) read_ks<KK>(nxt.b[3], bd + (fa.b[1] ^ 192u));
-    } else {
-        if (NTF > 2) read_kc<2>(nxt.b[2], bd);
-        if (NTF > 3) read_kc<3>(nxt.b[3], bd);
+    if (rd) {
+        if (B_KS) {
+            if (NTF > 2) read_ks<KK>(nxt.b[2], bd + (fa.b[1] ^ 128u));
+            if (NTF > 3) read_ks<KK>(nxt.b[3], bd + (fa.b[1] ^ 192u));
+        } else {
+            if (NTF > 2) read_kc<2>(nxt.b[2], bd);
+            if (NTF > 3) read_kc<3>(nxt.b[3], bd);
+        }
     }
     __builtin_amdgcn_sched_barrier(0);
     if (NTF > 1) mm(1, 1);
@@ -481,10 +487,10 @@ __device__ __forceinline__ void mma_loop(LB& lb, LA& la, int nk, char* smem, con
                 __builtin_amdgcn_sched_barrier(0);
                 lb.issue(smem + boff);
             }
-            if (NTF > 0) read_frags<NTF, A_KS, B_KS, 0>(f0, fa, noff);
         }
         __builtin_amdgcn_sched_barrier(0);
-        if (NTF > 0) mfma_step<NTF>(f1, acc);
+        // the matrix instructions of sub-step 3, with the first fragment reads of stage t+1 (if there is one) between them
+        if (NTF > 0) mfma_step_reading<NTF, A_KS, B_KS, 0>(f1, f0, fa, noff, acc, t + 1 < nk);
         __builtin_amdgcn_sched_barrier(0);
         if (t + 2 < nk) la.issue(smem + boff + kOperandBytes);   // the second operand's requests behind a burst of matrix work
     }
