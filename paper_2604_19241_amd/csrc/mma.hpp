@@ -218,6 +218,20 @@ __device__ __forceinline__ void mfma_step_reading(const Frags& cur, Frags& nxt, 
                                                               __builtin_bit_cast(bf16x8_t, cur.b[tf]), acc[tf][af], 0, 0, 0);
     };
     const uint32_t ad = (A_KS ? 0u : fa.a[KK]) + boff, bd = (B_KS ? fa.b[0] : fa.b[KK]) + boff;
+    auto rb = [&](int tf) {
+        if (!rd) return;
+        if (B_KS) {
+            if (tf == 0) read_ks<KK>(nxt.b[0], bd + fa.b[1]);
+            if (tf == 1) read_ks<KK>(nxt.b[1], bd + (fa.b[1] ^ 64u));
+            if (tf == 2) read_ks<KK>(nxt.b[2], bd + (fa.b[1] ^ 128u));
+            if (tf == 3) read_ks<KK>(nxt.b[3], bd + (fa.b[1] ^ 192u));
+        } else {
+            if (tf == 0) read_kc<0>(nxt.b[0], bd);
+            if (tf == 1) read_kc<1>(nxt.b[1], bd);
+            if (tf == 2) read_kc<2>(nxt.b[2], bd);
+            if (tf == 3) read_kc<3>(nxt.b[3], bd);
+        }
+    };
     if (NTF > 0) mm(0, 0);
     __builtin_amdgcn_sched_barrier(0);
     if (rd) {
@@ -232,33 +246,24 @@ __device__ __forceinline__ void mfma_step_reading(const Frags& cur, Frags& nxt, 
     __builtin_amdgcn_sched_barrier(0);
     if (NTF > 0) mm(0, 1);
     __builtin_amdgcn_sched_barrier(0);
-    if (rd) {
-        if (B_KS) {
-            if (NTF > 0) read_ks<KK>(nxt.b[0], bd + fa.b[1]);
-            if (NTF > 1) read_ks<KK>(nxt.b[1], bd + (fa.b[1] ^ 64u));
-        } else {
-            if (NTF > 0) read_kc<0>(nxt.b[0], bd);
-            if (NTF > 1) read_kc<1>(nxt.b[1], bd);
-        }
-    }
+    if (NTF > 0) rb(0);
     __builtin_amdgcn_sched_barrier(0);
     if (NTF > 1) mm(1, 0);
     __builtin_amdgcn_sched_barrier(0);
-    if (rd) {
-        if (B_KS) {
-            if (NTF > 2) read_ks<KK>(nxt.b[2], bd + (fa.b[1] ^ 128u));
-            if (NTF > 3) read_ks<KK>(nxt.b[3], bd + (fa.b[1] ^ 192u));
-        } else {
-            if (NTF > 2) read_kc<2>(nxt.b[2], bd);
-            if (NTF > 3) read_kc<3>(nxt.b[3], bd);
-        }
-    }
+    if (NTF > 1) rb(1);
     __builtin_amdgcn_sched_barrier(0);
     if (NTF > 1) mm(1, 1);
-#pragma unroll
-    for (int tf = 2; tf < NTF; ++tf) {
-        mm(tf, 0);
-        mm(tf, 1);
+    __builtin_amdgcn_sched_barrier(0);
+    if (NTF > 2) rb(2);
+    __builtin_amdgcn_sched_barrier(0);
+    if (NTF > 2) mm(2, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    if (NTF > 3) rb(3);
+    __builtin_amdgcn_sched_barrier(0);
+    if (NTF > 2) mm(2, 1);
+    if (NTF > 3) {
+        mm(3, 0);
+        mm(3, 1);
     }
 }
 
