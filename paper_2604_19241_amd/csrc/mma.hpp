@@ -232,35 +232,40 @@ __device__ __forceinline__ void mfma_step_reading(const Frags& cur, Frags& nxt, 
             if (tf == 3) read_kc<3>(nxt.b[3], bd);
         }
     };
+    auto ra = [&](int af) {
+        if (!rd) return;
+        if (A_KS) {
+            if (af == 0) read_ks<KK>(nxt.a[0], fa.a[0] + boff);
+            else read_ks<KK>(nxt.a[1], fa.a[1] + boff);
+        } else {
+            if (af == 0) read_kc<0>(nxt.a[0], ad);
+            else read_kc<1>(nxt.a[1], ad);
+        }
+    };
     if (NTF > 0) mm(0, 0);
     __builtin_amdgcn_sched_barrier(0);
-    if (rd) {
-        if (A_KS) {
-            read_ks<KK>(nxt.a[0], fa.a[0] + boff);
-            read_ks<KK>(nxt.a[1], fa.a[1] + boff);
-        } else {
-            read_kc<0>(nxt.a[0], ad);
-            read_kc<1>(nxt.a[1], ad);
-        }
-    }
+    ra(0);
     __builtin_amdgcn_sched_barrier(0);
     if (NTF > 0) mm(0, 1);
     __builtin_amdgcn_sched_barrier(0);
-    if (NTF > 0) rb(0);
+    ra(1);
     __builtin_amdgcn_sched_barrier(0);
     if (NTF > 1) mm(1, 0);
     __builtin_amdgcn_sched_barrier(0);
-    if (NTF > 1) rb(1);
+    if (NTF > 0) rb(0);
     __builtin_amdgcn_sched_barrier(0);
     if (NTF > 1) mm(1, 1);
     __builtin_amdgcn_sched_barrier(0);
-    if (NTF > 2) rb(2);
+    if (NTF > 1) rb(1);
     __builtin_amdgcn_sched_barrier(0);
     if (NTF > 2) mm(2, 0);
     __builtin_amdgcn_sched_barrier(0);
-    if (NTF > 3) rb(3);
+    if (NTF > 2) rb(2);
     __builtin_amdgcn_sched_barrier(0);
     if (NTF > 2) mm(2, 1);
+    __builtin_amdgcn_sched_barrier(0);
+    if (NTF > 3) rb(3);
+    __builtin_amdgcn_sched_barrier(0);
     if (NTF > 3) {
         mm(3, 0);
         mm(3, 1);
