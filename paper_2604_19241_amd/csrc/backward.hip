@@ -631,6 +631,7 @@ __device__ __forceinline__ void bwd_worker_body(const BwdParams& p, int phase, c
     const bool publishes = phase == -1 || phase == B_DXP;
     bool arrived = false;
     unsigned exhausted = 0;
+    int seen_e = -1;   // the expert whose dH tiles this worker last found complete
     if (threadIdx.x == 0) {
         if (phase == -1) worker_started(ctrl, home);
         s_task = fetch_task(ctrl, pass, home, exhausted, use_lists, use_tail);
@@ -681,9 +682,14 @@ __device__ __forceinline__ void bwd_worker_body(const BwdParams& p, int phase, c
                 // rows of the whole expert (a part of a split reduction carries only its own share)
                 const int rows_e = SPLIT ? p.offsets[e + 1] - p.offsets[e] : task.rows;
                 const int need = (rows_e + p.bm - 1) / p.bm * p.nct_dh;
-                if (threadIdx.x == 0) s_ok = wait_ge(p.flag_e + e, need, ctrl, p.spin_ticks);
-                __syncthreads();
-                if (s_ok) {
+                // a worker takes several of an expert's 72 output tiles in a row: the expert it has
+                // already seen complete (and acquired) needs no second look at the flag
+                if (e != seen_e) {
+                    if (threadIdx.x == 0) s_ok = wait_ge(p.flag_e + e, need, ctrl, p.spin_ticks);
+                    __syncthreads();
+                    if (s_ok) seen_e = e;
+                }
+                if (e == seen_e) {
                     if (type == B_DWD) dwd_task<ACC, SPLIT>(p, e, task.idx, ct, task.row0, task.rows, smem, &s_ok, issue);
                     else dwgu_task<ACC, SPLIT>(p, e, task.idx, ct, task.row0, task.rows, smem, &s_ok, issue);
                 }
